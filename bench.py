@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Throughput of the A-RIDE scoring pass on one MI355X.
+
+One "step" is one pass of the whole hot path over one learner batch (the "learner_batch"
+workload: 256 trajectories of 1..20 steps, 32 action tokens per step, V = 32128 bf16
+logits; replay buffer of 65536 entries, 1024 draws):
+
+    score_logits -> retrace_targets -> compute_priorities -> sample_prioritized
+                 -> update_priorities (scatter + index rebuild)
+
+All inputs are synthetic, seeded, and resident in HBM before the timed region starts.
+Prints ONE JSON line: whole-job trajectory-steps/s, the HBM roofline of the dominant
+kernel (the logit sweep) from HIP events recorded inside the timed region, and the CPU
+oracle timed on a bounded sample of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="workload index (1 = learner batch)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the CPU sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_14803_amd import binding as b
+    from paper_2410_14803_amd import synth
+
+    b.lib()   # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    assert cfg.V > 0 and cfg.M > 0, "bench runs a workload with logits and a replay buffer"
+    seed = synth.BASE_SEED + cfg.index
+    off_np = synth.trajectory_offsets(cfg, seed)
+    N = int(off_np[-1]); R = N * cfg.A; B = cfg.B; K = cfg.K; M = cfg.M
+    off = torch.as_tensor(off_np, device=dev)
+    logits = synth.logits_bf16(R, cfg.V, seed + 1, dev, heavy_tail=cfg.heavy_tail)
+    tokens = synth.action_tokens(logits, seed + 2)
+    si = synth.step_inputs(cfg, off_np, seed + 4, dev)
+    ws = b.Workspace(M, device=dev)
+    f = lambda n: torch.empty(n, device=dev)
+    tok_logp, tok_ent, step_logp, step_ent = f(R), f(R), f(N), f(N)
+    target, td, rho, step_prio, traj_prio = f(N), f(N), f(N), f(N), f(B)
+    idx = torch.empty(K, dtype=torch.int64, device=dev)
+    prob = f(K)
+    ent_scale = float(cfg.A * np.log(cfg.V))
+
+    # input preparation (untimed): behaviour log-probs lag the policy's by seeded noise, and the
+    # replay buffer starts from seeded priorities
+    b.score_logits(logits, tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent, step_logp=step_logp, step_ent=step_ent)
+    logmu = (step_logp + si["mu_noise"]).contiguous()
+    weights = torch.zeros(M, device=dev)
+    p0 = synth.replay_priorities(M, cfg.replay, seed + 5, dev)
+    b.update_priorities(weights, torch.arange(M, device=dev), p0, cfg.alpha, ws)
+    total_iters = args.steps + args.warmup
+    uni = synth.uniforms(K * total_iters, seed + 6, dev).view(total_iters, K)
+    prio_src = (torch.arange(K, device=dev) % N)   # first K step priorities, wrapping if N < K
+    torch.cuda.synchronize()
+
+    def one_step(i, ev=None):
+        if ev is not None:
+            ev[0].record()
+        b.score_logits(logits, tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
+                       step_logp=step_logp, step_ent=step_ent)
+        if ev is not None:
+            ev[1].record()
+        b.retrace_targets(step_logp, logmu, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"],
+                          target=target, td=td, rho=rho)
+        b.compute_priorities(td, rho, step_ent, off, cfg.w, td_scale=2.0, ent_scale=ent_scale,
+                             step_prio=step_prio, traj_prio=traj_prio)
+        b.sample_prioritized(weights, uni[i], ws, idx, prob)
+        b.update_priorities(weights, idx, step_prio[prio_src] if N < K else step_prio[:K], cfg.alpha, ws)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0, f"status flags {st.flags:#x} rc {rc}"
+
+    ms_per_step = elapsed / args.steps * 1e3
+    value = N * args.steps / elapsed
+    # dominant kernel: the logit sweep.  Algorithmic bytes per launch: every bf16 logit once,
+    # one int32 token per row, two fp32 results per row.
+    sweep_ms = sum(a.elapsed_time(c) for a, c in events) / args.steps
+    alg_bytes = R * cfg.V * 2 + R * 4 + R * 8
+    achieved = alg_bytes / (sweep_ms * 1e-3) / 1e9
+    out = {
+        "metric": METRIC, "value": value, "unit": "trajectory-steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": B, "traj_steps": N,
+                   "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
+                   "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha},
+        "roofline": {"bound": "hbm", "kernel": "k_score_rows (+ per-step sums)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(os.cpu_count() or 1, 16)
+        host = lambda t: t.detach().cpu().numpy()
+        rows_probe = min(R, 2 * cfg.A)
+        bits = lambda r: logits[:r].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        tp0 = time.perf_counter()
+        oracle.score_logits(bits(rows_probe), host(tokens[:rows_probe]), cfg.A, nthreads=threads)
+        per_row = (time.perf_counter() - tp0) / rows_probe
+        # whole trajectories, as many as fit the time budget
+        want_rows = max(cfg.A, int(args.cpu_seconds / max(per_row, 1e-9)))
+        nb = int(np.searchsorted(off_np * cfg.A, want_rows, side="right")) - 1
+        nb = max(1, min(B, nb))
+        n_s = int(off_np[nb]); r_s = n_s * cfg.A
+        lb, tk = bits(r_s), host(tokens[:r_s])
+        lm, rw, vv, qq = host(logmu[:n_s]), host(si["reward"][:n_s]), host(si["value"][:n_s]), host(si["q"][:n_s])
+        w_host, u_host = host(weights).copy(), host(uni[0])
+        tc0 = time.perf_counter()
+        o = oracle.score_logits(lb, tk, cfg.A, nthreads=threads)
+        ort = oracle.retrace_targets(o["step_logp"], lm, rw, vv, off_np[:nb + 1], cfg.gamma, cfg.lam, q=qq)
+        opr = oracle.compute_priorities(ort["td"], ort["rho"], o["step_ent"], off_np[:nb + 1], *cfg.w,
+                                        td_scale=2.0, ent_scale=ent_scale)
+        oi, _, _ = oracle.sample_prioritized(w_host, u_host)
+        pk = opr["step_prio"][np.arange(K) % n_s].astype(np.float32)
+        oracle.update_priorities(w_host, oi, pk, cfg.alpha)
+        tc1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": n_s / (tc1 - tc0), "unit": "trajectory-steps/s", "cores": threads,
+                               "kind": "oracle", "seconds": tc1 - tc0,
+                               "sample": f"first {nb} trajectories of the batch ({n_s} steps, {r_s} logit rows), "
+                                         f"whole path incl. one {K}-draw sample and update on the {M}-entry buffer"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,170 @@
+"""ctypes binding of libaride.so (the C ABI declared in include/aride.h).
+
+Argument marshalling only: every function takes torch CUDA tensors (or None for
+nullable arguments), checks dtype/contiguity, and passes raw device pointers plus the
+current torch stream to the library.  Nothing is computed here and there is no
+fallback: if the shared library has not been built, lib() raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaride.so")
+_lib = None
+
+OK = 0
+E_NULL, E_SHAPE, E_ALIGN, E_RANGE, E_ZERO_MASS, E_WORKSPACE, E_HIP = -1, -2, -3, -4, -5, -6, -7
+ST_BAD_TOKEN, ST_BAD_WEIGHT, ST_ZERO_MASS, ST_BAD_INDEX, ST_BAD_UNIFORM = 1, 2, 4, 8, 16
+MAX_REPLAY = 1 << 24
+
+EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
+           "aride_score_logits", "aride_retrace_targets", "aride_compute_priorities",
+           "aride_update_priorities", "aride_sample_prioritized"]
+
+
+class RetraceCfg(ctypes.Structure):
+    _fields_ = [("gamma", ctypes.c_float), ("lam", ctypes.c_float)]
+
+
+class PrioCfg(ctypes.Structure):
+    _fields_ = [("w_td", ctypes.c_float), ("w_rho", ctypes.c_float), ("w_ent", ctypes.c_float),
+                ("td_scale", ctypes.c_float), ("ent_scale", ctypes.c_float), ("eps", ctypes.c_float),
+                ("truncate_rho", ctypes.c_int32)]
+
+
+class Status(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32), ("total", ctypes.c_uint64),
+                ("wmax", ctypes.c_float), ("exponent", ctypes.c_int32)]
+
+
+class ArideError(RuntimeError):
+    def __init__(self, fn, rc):
+        super().__init__(f"{fn} failed with code {rc}")
+        self.rc = rc
+
+
+def lib():
+    """Loads libaride.so (raises FileNotFoundError / OSError if it is not built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2410_14803_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    L.aride_workspace_bytes.restype = ctypes.c_int
+    L.aride_workspace_bytes.argtypes = [i64, ctypes.POINTER(sz)]
+    L.aride_workspace_init.restype = ctypes.c_int
+    L.aride_workspace_init.argtypes = [vp, sz, vp]
+    L.aride_status_read.restype = ctypes.c_int
+    L.aride_status_read.argtypes = [vp, ctypes.POINTER(Status), vp]
+    L.aride_score_logits.restype = ctypes.c_int
+    L.aride_score_logits.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.aride_retrace_targets.restype = ctypes.c_int
+    L.aride_retrace_targets.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, RetraceCfg, vp, vp, vp, vp]
+    L.aride_compute_priorities.restype = ctypes.c_int
+    L.aride_compute_priorities.argtypes = [vp, vp, vp, vp, i64, i64, PrioCfg, vp, vp, vp]
+    L.aride_update_priorities.restype = ctypes.c_int
+    L.aride_update_priorities.argtypes = [vp, i64, vp, vp, i64, f32, vp, sz, vp]
+    L.aride_sample_prioritized.restype = ctypes.c_int
+    L.aride_sample_prioritized.argtypes = [vp, i64, vp, sz, vp, i64, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def _p(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise ArideError(fn, rc)
+
+
+def workspace_bytes(M: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check("aride_workspace_bytes", lib().aride_workspace_bytes(int(M), ctypes.byref(out)))
+    return out.value
+
+
+class Workspace:
+    """Device workspace (status block + replay index for capacity M), caller-owned memory."""
+
+    def __init__(self, M: int = 0, device="cuda"):
+        self.M = int(M)
+        self.nbytes = workspace_bytes(M)
+        self.buf = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
+        assert self.buf.data_ptr() % 256 == 0
+        _check("aride_workspace_init", lib().aride_workspace_init(_p(self.buf), self.nbytes, _stream()))
+
+    @property
+    def ptr(self):
+        return ctypes.c_void_p(self.buf.data_ptr())
+
+    def status(self):
+        """Synchronising read of the status block; returns (Status, rc)."""
+        st = Status()
+        rc = lib().aride_status_read(self.ptr, ctypes.byref(st), _stream())
+        return st, rc
+
+
+def score_logits(logits, tokens, A, ws, tok_logp=None, tok_ent=None, step_logp=None, step_ent=None, V=None):
+    """logits: bf16 [R, row_stride]; tokens int32 [R]; outputs are written in place."""
+    assert logits.dtype == torch.bfloat16 and logits.dim() == 2
+    R, stride = logits.shape
+    V = stride if V is None else int(V)
+    rc = lib().aride_score_logits(_p(logits), R, V, stride, _p(tokens, torch.int32), int(A),
+                                  _p(tok_logp, torch.float32), _p(tok_ent, torch.float32),
+                                  _p(step_logp, torch.float32), _p(step_ent, torch.float32),
+                                  ws.ptr, ws.nbytes, _stream())
+    _check("aride_score_logits", rc)
+
+
+def retrace_targets(logp_pi, logp_mu, reward, value, traj_offsets, gamma, lam, q=None, boot=None,
+                    target=None, td=None, rho=None):
+    B = traj_offsets.numel() - 1
+    N = logp_pi.numel()
+    f = torch.float32
+    rc = lib().aride_retrace_targets(_p(logp_pi, f), _p(logp_mu, f), _p(reward, f), _p(value, f), _p(q, f),
+                                     _p(boot, f), _p(traj_offsets, torch.int32), B, N,
+                                     RetraceCfg(float(gamma), float(lam)), _p(target, f), _p(td, f),
+                                     _p(rho, f), _stream())
+    _check("aride_retrace_targets", rc)
+
+
+def compute_priorities(td, rho, ent, traj_offsets, w, td_scale=1.0, ent_scale=1.0, eps=0.0,
+                       truncate_rho=True, step_prio=None, traj_prio=None):
+    B = traj_offsets.numel() - 1
+    N = td.numel()
+    f = torch.float32
+    cfg = PrioCfg(float(w[0]), float(w[1]), float(w[2]), float(td_scale), float(ent_scale), float(eps),
+                  int(bool(truncate_rho)))
+    rc = lib().aride_compute_priorities(_p(td, f), _p(rho, f), _p(ent, f), _p(traj_offsets, torch.int32),
+                                        B, N, cfg, _p(step_prio, f), _p(traj_prio, f), _stream())
+    _check("aride_compute_priorities", rc)
+
+
+def update_priorities(weights, idx, prio, alpha, ws):
+    """weights fp32 [M] updated in place; idx int64 [K] / prio fp32 [K] may be None (rebuild only)."""
+    K = 0 if idx is None else idx.numel()
+    rc = lib().aride_update_priorities(_p(weights, torch.float32), weights.numel(), _p(idx, torch.int64),
+                                       _p(prio, torch.float32), K, float(alpha), ws.ptr, ws.nbytes, _stream())
+    _check("aride_update_priorities", rc)
+
+
+def sample_prioritized(weights, uniforms, ws, idx_out, prob_out=None):
+    rc = lib().aride_sample_prioritized(_p(weights, torch.float32), weights.numel(), ws.ptr, ws.nbytes,
+                                        _p(uniforms, torch.float64), uniforms.numel(),
+                                        _p(idx_out, torch.int64), _p(prob_out, torch.float32), _stream())
+    _check("aride_sample_prioritized", rc)

@@ -1,0 +1,150 @@
+// C ABI of the A-RIDE scoring library: host-side argument validation and kernel launches.
+// Nothing here allocates, frees or waits (aride_status_read excepted, as documented).
+#include "aride.h"
+#include "aride_device.h"
+
+namespace aride {
+hipError_t score_logits_launch(const uint16_t*, long long, int, long long, const int*, int, float*,
+                               float*, float*, float*, uint32_t*, int, hipStream_t);
+hipError_t retrace_launch(const float*, const float*, const float*, const float*, const float*,
+                          const float*, const int*, int, int, float, float, float*, float*, float*,
+                          hipStream_t);
+hipError_t priorities_launch(const float*, const float*, const float*, const int*, int, int, float,
+                             float, float, float, float, float, int, float*, float*, hipStream_t);
+hipError_t update_launch(float*, long long, const long long*, const float*, int, float, WsHeader*,
+                         unsigned long long*, hipStream_t);
+hipError_t sample_launch(const float*, long long, const WsHeader*, const unsigned long long*,
+                         const double*, int, long long*, float*, uint32_t*, hipStream_t);
+
+static_assert(sizeof(aride_status) == 24, "status block layout");
+static_assert(sizeof(WsHeader) == sizeof(aride_status), "device header mirrors the status block");
+
+__global__ void k_fill_u64(unsigned long long* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0ull;
+}
+
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline size_t replay_blocks(int64_t M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
+static inline size_t index_bytes(int64_t M) { return round_up(replay_blocks(M) * 8, 256); }
+static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+}  // namespace aride
+
+using namespace aride;
+
+extern "C" {
+
+int aride_workspace_bytes(int64_t M, size_t* out_bytes) {
+    if (!out_bytes) return ARIDE_E_NULL;
+    if (M < 0) return ARIDE_E_SHAPE;
+    if (M > ARIDE_MAX_REPLAY) return ARIDE_E_RANGE;
+    *out_bytes = kHeaderBytes + index_bytes(M);
+    return ARIDE_OK;
+}
+
+int aride_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+    if (!ws || misaligned(ws, 256) || ws_bytes < kHeaderBytes) return ARIDE_E_WORKSPACE;
+    const size_t n = ws_bytes / 8;
+    size_t want = (n + 255) / 256;
+    const unsigned g = (unsigned)(want > 1024 ? 1024 : (want < 1 ? 1 : want));
+    hipLaunchKernelGGL(k_fill_u64, dim3(g), dim3(256), 0, (hipStream_t)stream,
+                       (unsigned long long*)ws, n);
+    return hipGetLastError() == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_status_read(const void* ws, aride_status* out, void* stream) {
+    if (!ws || !out) return ARIDE_E_NULL;
+    if (hipMemcpyAsync(out, ws, sizeof(aride_status), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
+        return ARIDE_E_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ARIDE_E_HIP;
+    return (out->flags & ARIDE_ST_ZERO_MASS) ? ARIDE_E_ZERO_MASS : ARIDE_OK;
+}
+
+int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                       const int32_t* tokens, int32_t A, float* tok_logp, float* tok_ent,
+                       float* step_logp, float* step_ent, void* ws, size_t ws_bytes, void* stream) {
+    if (R < 0 || V <= 0 || A <= 0 || row_stride < V || R % A != 0) return ARIDE_E_SHAPE;
+    if (V > 0x7fffffffLL || R > (int64_t)1 << 40) return ARIDE_E_RANGE;
+    if (!ws || misaligned(ws, 256)) return ARIDE_E_WORKSPACE;
+    if (R == 0) return ARIDE_OK;
+    if (!logits_bf16 || !tokens) return ARIDE_E_NULL;
+    if (misaligned(logits_bf16, 16) || misaligned(tokens, 4)) return ARIDE_E_ALIGN;
+    if ((step_logp && !tok_logp) || (step_ent && !tok_ent)) return ARIDE_E_NULL;
+    if (ws_bytes < kHeaderBytes) return ARIDE_E_WORKSPACE;
+    hipError_t err = score_logits_launch((const uint16_t*)logits_bf16, R, (int)V, row_stride, tokens, A,
+                                         tok_logp, tok_ent, step_logp, step_ent, (uint32_t*)ws, 0,
+                                         (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_retrace_targets(const float* logp_pi, const float* logp_mu, const float* reward,
+                          const float* value, const float* q, const float* boot,
+                          const int32_t* traj_offsets, int64_t B, int64_t N, aride_retrace_cfg cfg,
+                          float* target, float* td, float* rho, void* stream) {
+    if (B < 0 || N < 0) return ARIDE_E_SHAPE;
+    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (B == 0) return ARIDE_OK;
+    if (!traj_offsets) return ARIDE_E_NULL;
+    if (N > 0 && (!logp_pi || !logp_mu || !reward || !value)) return ARIDE_E_NULL;
+    hipError_t err = retrace_launch(logp_pi, logp_mu, reward, value, q, boot, traj_offsets, (int)B,
+                                    (int)N, cfg.gamma, cfg.lambda, target, td, rho, (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_compute_priorities(const float* td, const float* rho, const float* ent,
+                             const int32_t* traj_offsets, int64_t B, int64_t N, aride_prio_cfg cfg,
+                             float* step_prio, float* traj_prio, void* stream) {
+    if (B < 0 || N < 0) return ARIDE_E_SHAPE;
+    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (!(cfg.td_scale != 0.f) || !(cfg.ent_scale != 0.f)) return ARIDE_E_RANGE;
+    if (B == 0) return ARIDE_OK;
+    if (!traj_offsets) return ARIDE_E_NULL;
+    if (N > 0 && (!td || !rho || !ent)) return ARIDE_E_NULL;
+    hipError_t err = priorities_launch(td, rho, ent, traj_offsets, (int)B, (int)N, cfg.w_td, cfg.w_rho,
+                                       cfg.w_ent, cfg.td_scale, cfg.ent_scale, cfg.eps,
+                                       cfg.truncate_rho != 0, step_prio, traj_prio, (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+static int check_replay(const float* weights, int64_t M, const void* ws, size_t ws_bytes) {
+    if (M <= 0) return ARIDE_E_SHAPE;
+    if (M > ARIDE_MAX_REPLAY) return ARIDE_E_RANGE;
+    if (!weights) return ARIDE_E_NULL;
+    if (misaligned(weights, 16)) return ARIDE_E_ALIGN;
+    if (!ws || misaligned(ws, 256) || ws_bytes < kHeaderBytes + index_bytes(M)) return ARIDE_E_WORKSPACE;
+    return ARIDE_OK;
+}
+
+int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const float* prio,
+                            int64_t K, float alpha, void* ws, size_t ws_bytes, void* stream) {
+    if (K < 0) return ARIDE_E_SHAPE;
+    int rc = check_replay(weights, M, ws, ws_bytes);
+    if (rc != ARIDE_OK) return rc;
+    if (K >= (1 << 23) || !(alpha >= 0.f)) return ARIDE_E_RANGE;
+    if (K > 0 && (!idx || !prio)) return ARIDE_E_NULL;
+    if (K > 0 && misaligned(idx, 8)) return ARIDE_E_ALIGN;
+    WsHeader* hdr = (WsHeader*)ws;
+    unsigned long long* cum = (unsigned long long*)((char*)ws + kHeaderBytes);
+    hipError_t err = update_launch(weights, M, (const long long*)idx, prio, (int)K, alpha, hdr, cum,
+                                   (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t ws_bytes,
+                             const double* uniforms, int64_t K, int64_t* idx_out, float* prob_out,
+                             void* stream) {
+    if (K < 0) return ARIDE_E_SHAPE;
+    int rc = check_replay(weights, M, ws, ws_bytes);
+    if (rc != ARIDE_OK) return rc;
+    if (K > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (K == 0) return ARIDE_OK;
+    if (!uniforms || !idx_out) return ARIDE_E_NULL;
+    if (misaligned(uniforms, 8) || misaligned(idx_out, 8)) return ARIDE_E_ALIGN;
+    const WsHeader* hdr = (const WsHeader*)ws;
+    const unsigned long long* cum = (const unsigned long long*)((char*)ws + kHeaderBytes);
+    hipError_t err = sample_launch(weights, M, hdr, cum, uniforms, (int)K, (long long*)idx_out, prob_out,
+                                   (uint32_t*)ws, (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, sizes its workspace as documented and rejects bad
+arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_14803_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = ctypes.c_void_p
+
+
+@pytest.fixture(scope="module")
+def L():
+    return b.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    text = open(os.path.join(ROOT, "include", "aride.h")).read()
+    declared = sorted(set(re.findall(r"^int\s+(aride_\w+)\s*\(", text, flags=re.M)))
+    assert declared == sorted(b.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_error_codes_match_header():
+    text = open(os.path.join(ROOT, "include", "aride.h")).read()
+    codes = dict(re.findall(r"#define\s+(ARIDE_E_\w+)\s+(-?\d+)", text))
+    assert int(codes["ARIDE_E_NULL"]) == b.E_NULL and int(codes["ARIDE_E_SHAPE"]) == b.E_SHAPE
+    assert int(codes["ARIDE_E_ALIGN"]) == b.E_ALIGN and int(codes["ARIDE_E_RANGE"]) == b.E_RANGE
+    assert int(codes["ARIDE_E_ZERO_MASS"]) == b.E_ZERO_MASS and int(codes["ARIDE_E_WORKSPACE"]) == b.E_WORKSPACE
+    assert int(codes["ARIDE_E_HIP"]) == b.E_HIP
+    assert ctypes.sizeof(b.Status) == 24 and ctypes.sizeof(b.PrioCfg) == 28 and ctypes.sizeof(b.RetraceCfg) == 8
+
+
+def test_workspace_bytes(L):
+    assert b.workspace_bytes(0) == 256
+    assert b.workspace_bytes(1) == 512                       # one block sum, rounded to 256
+    assert b.workspace_bytes(256 * 32) == 256 + 256
+    assert b.workspace_bytes(256 * 32 + 1) == 256 + 512
+    assert b.workspace_bytes(1 << 24) == 256 + 8 * 65536
+    out = ctypes.c_size_t(0)
+    assert L.aride_workspace_bytes(-1, ctypes.byref(out)) == b.E_SHAPE
+    assert L.aride_workspace_bytes((1 << 24) + 1, ctypes.byref(out)) == b.E_RANGE
+    assert L.aride_workspace_bytes(10, None) == b.E_NULL
+
+
+def test_score_logits_rejects_bad_arguments(L):
+    ws, x, t = P(4096), P(4096), P(8192)   # never dereferenced: every call fails validation first
+    f = L.aride_score_logits
+    assert f(x, 4, 10, 10, t, 3, None, None, None, None, ws, 256, None) == b.E_SHAPE    # R % A
+    assert f(x, -1, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.E_SHAPE
+    assert f(x, 4, 0, 10, t, 1, None, None, None, None, ws, 256, None) == b.E_SHAPE
+    assert f(x, 4, 10, 9, t, 1, None, None, None, None, ws, 256, None) == b.E_SHAPE     # stride < V
+    assert f(x, 4, 10, 10, t, 0, None, None, None, None, ws, 256, None) == b.E_SHAPE
+    assert f(x, 4, 1 << 31, 1 << 31, t, 1, None, None, None, None, ws, 256, None) == b.E_RANGE
+    assert f(None, 4, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.E_NULL
+    assert f(x, 4, 10, 10, None, 1, None, None, None, None, ws, 256, None) == b.E_NULL
+    assert f(P(4098), 4, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.E_ALIGN
+    assert f(x, 4, 10, 10, t, 1, None, None, None, None, None, 256, None) == b.E_WORKSPACE
+    assert f(x, 4, 10, 10, t, 1, None, None, None, None, P(4100), 256, None) == b.E_WORKSPACE
+    assert f(x, 4, 10, 10, t, 1, None, None, None, None, ws, 100, None) == b.E_WORKSPACE
+    assert f(x, 4, 10, 10, t, 1, None, None, P(64), None, ws, 256, None) == b.E_NULL    # step sums need tok arrays
+    assert f(x, 0, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.OK         # empty: no-op
+
+
+def test_retrace_and_priorities_reject_bad_arguments(L):
+    a = P(4096)
+    cfg = b.RetraceCfg(0.9, 0.95)
+    f = L.aride_retrace_targets
+    assert f(a, a, a, a, None, None, a, -1, 4, cfg, a, a, a, None) == b.E_SHAPE
+    assert f(a, a, a, a, None, None, a, 2, -4, cfg, a, a, a, None) == b.E_SHAPE
+    assert f(a, a, a, a, None, None, a, 2, 1 << 31, cfg, a, a, a, None) == b.E_RANGE
+    assert f(a, a, a, a, None, None, None, 2, 4, cfg, a, a, a, None) == b.E_NULL
+    assert f(None, a, a, a, None, None, a, 2, 4, cfg, a, a, a, None) == b.E_NULL
+    assert f(a, a, a, a, None, None, a, 0, 0, cfg, a, a, a, None) == b.OK
+    g = L.aride_compute_priorities
+    pc = b.PrioCfg(1, 0.5, 0.1, 1, 1, 0, 1)
+    assert g(a, a, a, a, -1, 4, pc, a, a, None) == b.E_SHAPE
+    assert g(a, a, a, None, 2, 4, pc, a, a, None) == b.E_NULL
+    assert g(a, None, a, a, 2, 4, pc, a, a, None) == b.E_NULL
+    assert g(a, a, a, a, 2, 4, b.PrioCfg(1, 1, 1, 0, 1, 0, 1), a, a, None) == b.E_RANGE
+    assert g(a, a, a, a, 2, 4, b.PrioCfg(1, 1, 1, 1, 0, 0, 1), a, a, None) == b.E_RANGE
+    assert g(a, a, a, a, 0, 0, pc, a, a, None) == b.OK
+
+
+def test_replay_rejects_bad_arguments(L):
+    w, ws, a = P(4096), P(8192), P(16384)
+    need = b.workspace_bytes(1000)
+    u = L.aride_update_priorities
+    assert u(w, 0, a, a, 4, 0.6, ws, need, None) == b.E_SHAPE
+    assert u(w, 1000, a, a, -1, 0.6, ws, need, None) == b.E_SHAPE
+    assert u(w, (1 << 24) + 1, a, a, 4, 0.6, ws, 1 << 30, None) == b.E_RANGE
+    assert u(None, 1000, a, a, 4, 0.6, ws, need, None) == b.E_NULL
+    assert u(P(4100), 1000, a, a, 4, 0.6, ws, need, None) == b.E_ALIGN
+    assert u(w, 1000, a, a, 4, 0.6, ws, need - 1, None) == b.E_WORKSPACE
+    assert u(w, 1000, a, a, 4, 0.6, None, need, None) == b.E_WORKSPACE
+    assert u(w, 1000, a, a, 4, -0.5, ws, need, None) == b.E_RANGE
+    assert u(w, 1000, a, a, 4, float("nan"), ws, need, None) == b.E_RANGE
+    assert u(w, 1000, a, a, 1 << 23, 0.6, ws, need, None) == b.E_RANGE
+    assert u(w, 1000, None, a, 4, 0.6, ws, need, None) == b.E_NULL
+    assert u(w, 1000, a, None, 4, 0.6, ws, need, None) == b.E_NULL
+    s = L.aride_sample_prioritized
+    assert s(w, 1000, ws, need, a, -1, a, None, None) == b.E_SHAPE
+    assert s(w, 0, ws, need, a, 4, a, None, None) == b.E_SHAPE
+    assert s(w, 1000, ws, need - 8, a, 4, a, None, None) == b.E_WORKSPACE
+    assert s(w, 1000, ws, need, None, 4, a, None, None) == b.E_NULL
+    assert s(w, 1000, ws, need, a, 4, None, None, None) == b.E_NULL
+    assert s(w, 1000, ws, need, P(16388), 4, a, None, None) == b.E_ALIGN
+    assert s(w, 1000, ws, need, a, 0, a, None, None) == b.OK
+    assert L.aride_workspace_init(None, 256, None) == b.E_WORKSPACE
+    assert L.aride_workspace_init(ws, 100, None) == b.E_WORKSPACE
+    assert L.aride_status_read(None, None, None) == b.E_NULL

@@ -1,0 +1,136 @@
+"""GPU parity: aride_retrace_targets and aride_compute_priorities against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_14803_amd import binding as b
+from paper_2410_14803_amd import synth
+from _util import assert_close, npf
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def gpu_retrace(lp, lm, r, v, off, gamma, lam, q=None, boot=None):
+    N = lp.numel()
+    out = {k: torch.full((N,), 7.0, device=DEV) for k in ("target", "td", "rho")}
+    b.retrace_targets(lp, lm, r, v, off, gamma, lam, q=q, boot=boot, **out)
+    torch.cuda.synchronize()
+    return {k: npf(t) for k, t in out.items()}
+
+
+def gpu_prio(td, rho, ent, off, w, **kw):
+    N, B = td.numel(), off.numel() - 1
+    sp = torch.full((N,), 7.0, device=DEV)
+    tp = torch.full((B,), 7.0, device=DEV)
+    b.compute_priorities(td, rho, ent, off, w, step_prio=sp, traj_prio=tp, **kw)
+    torch.cuda.synchronize()
+    return npf(sp), npf(tp)
+
+
+def make_case(lens, seed, cfg):
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    N = int(off_np[-1])
+    lp = synth.policy_logprobs(N, seed, DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 1, DEV)
+    lm = lp + si["mu_noise"]
+    g = torch.Generator(device=DEV); g.manual_seed(seed + 2)
+    boot = torch.rand(len(lens), generator=g, device=DEV) - 0.5
+    return off_np, torch.as_tensor(off_np, device=DEV), lp, lm, si, boot
+
+
+def check_retrace(oracle, off_np, off, lp, lm, si, boot, gamma, lam, tag):
+    for use_q in (False, True):
+        for use_boot in (False, True):
+            q = si["q"] if use_q else None
+            bt = boot if use_boot else None
+            got = gpu_retrace(lp, lm, si["reward"], si["value"], off, gamma, lam, q=q, boot=bt)
+            want = oracle.retrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, gamma,
+                                          lam, q=None if q is None else npf(q), boot=None if bt is None else npf(bt))
+            for k in ("target", "td", "rho"):
+                assert_close(got[k], want[k], 1.0, f"{tag} q={use_q} boot={use_boot} {k}")
+    return got, want
+
+
+@pytest.mark.parametrize("lens", [
+    [1], [2], [63], [64], [65], [127, 128, 129], [1, 1, 1, 1, 1], [0, 5, 0, 0, 7, 0],
+    [300, 1, 64, 1000, 2, 191, 192, 193], list(range(1, 80)),
+])
+def test_chunk_boundaries_and_ragged_lengths(oracle, lens):
+    print(f"case lens={lens[:8]}...", flush=True)
+    cfg = synth.CONFIGS[3]
+    case = make_case(lens, 300 + len(lens), cfg)
+    check_retrace(oracle, *case, gamma=0.99, lam=1.0, tag=f"lens{len(lens)}")
+    check_retrace(oracle, *case, gamma=0.9, lam=0.95, tag=f"lens{len(lens)}b")
+
+
+def test_special_cases_on_gpu():
+    # closed forms, no oracle: lambda=0 is one-step TD; pi==mu with lambda=1 is the discounted return
+    T = 200
+    off = torch.tensor([0, T], dtype=torch.int32, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    lp = -torch.rand(T, generator=g, device=DEV)
+    lm = lp + torch.randn(T, generator=g, device=DEV)
+    r = (torch.rand(T, generator=g, device=DEV) < 0.1).float()
+    v = torch.rand(T, generator=g, device=DEV)
+    out = gpu_retrace(lp, lm, r, v, off, 0.9, 0.0)
+    vn = torch.cat([v[1:], torch.zeros(1, device=DEV)])
+    assert_close(out["target"], npf(r + 0.9 * vn), 1.0, "lambda0")
+    out = gpu_retrace(lp, lp.clone(), r, v, off, 0.99, 1.0)
+    rr = npf(r).astype(np.float64)
+    G = np.zeros(T)
+    acc = 0.0
+    for t in range(T - 1, -1, -1):
+        acc = rr[t] + 0.99 * acc
+        G[t] = acc
+    assert_close(out["target"], G, 1.0, "monte-carlo")
+
+
+@pytest.mark.parametrize("ci", [0, 1, 3])
+def test_config_shapes(oracle, ci):
+    cfg = synth.CONFIGS[ci]
+    seed = synth.BASE_SEED + cfg.index
+    off_np = synth.trajectory_offsets(cfg, seed)
+    N = int(off_np[-1])
+    print(f"config{ci} B={cfg.B} N={N}", flush=True)
+    off = torch.as_tensor(off_np, device=DEV)
+    lp = synth.policy_logprobs(N, seed + 3, DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 4, DEV)
+    lm = lp + si["mu_noise"]
+    got, want = check_retrace(oracle, off_np, off, lp, lm, si, si["boot"], cfg.gamma, cfg.lam, f"config{ci}")
+    if ci == 3:
+        assert (want["rho"] > 1).mean() > 0.3      # a good share of ratios truncate
+    # priorities on the oracle's td / rho (as fp32) so only this kernel is under test
+    td = torch.as_tensor(want["td"].astype(np.float32), device=DEV)
+    rho = torch.as_tensor(want["rho"].astype(np.float32), device=DEV)
+    ent = torch.rand(N, device=DEV) * 8
+    for trunc in (True, False):
+        sp, tp = gpu_prio(td, rho, ent, off, cfg.w, td_scale=2.0, ent_scale=8.0, eps=1e-3, truncate_rho=trunc)
+        w = oracle.compute_priorities(npf(td), npf(rho), npf(ent), off_np, *cfg.w, td_scale=2.0, ent_scale=8.0,
+                                      eps=1e-3, truncate_rho=trunc)
+        assert_close(sp, w["step_prio"], 1.0, f"config{ci} step_prio trunc={trunc}")
+        assert_close(tp, w["traj_prio"], 1.0, f"config{ci} traj_prio trunc={trunc}")
+
+
+def test_priorities_empty_and_single(oracle):
+    off_np = np.array([0, 0, 1, 1, 70, 70], np.int32)
+    off = torch.as_tensor(off_np, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(9)
+    td = torch.randn(70, generator=g, device=DEV)
+    rho = torch.exp(torch.randn(70, generator=g, device=DEV))
+    ent = torch.rand(70, generator=g, device=DEV)
+    sp, tp = gpu_prio(td, rho, ent, off, (1.0, 0.5, 0.1))
+    w = oracle.compute_priorities(npf(td), npf(rho), npf(ent), off_np, 1.0, 0.5, 0.1)
+    assert_close(sp, w["step_prio"], 1.0, "step_prio")
+    assert_close(tp, w["traj_prio"], 1.0, "traj_prio")
+    assert tp[0] == 0 and tp[2] == 0 and tp[4] == 0
+
+
+def test_nullable_outputs_are_skipped():
+    off = torch.tensor([0, 5], dtype=torch.int32, device=DEV)
+    x = torch.zeros(5, device=DEV)
+    tgt = torch.full((5,), 3.0, device=DEV)
+    b.retrace_targets(x, x, x + 1, x, off, 0.5, 0.5, target=tgt)   # td, rho NULL
+    b.compute_priorities(x, x, x, off, (1, 1, 1))                   # both outputs NULL
+    torch.cuda.synchronize()
+    assert torch.all(tgt != 3.0)
