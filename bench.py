@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = learner batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the CPU sample")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -106,6 +108,19 @@ def main():
     st, rc = ws.status()
     assert rc == b.OK and st.flags == 0, f"status flags {st.flags:#x} rc {rc}"
 
+    if args.copy_probe:
+        import ctypes
+        probe = ctypes.CDLL(os.path.join(ROOT, "paper_2410_14803_amd", "libaride_probe.so"))
+        probe.aride_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            rcp = probe.aride_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(),
+                                         torch.cuda.current_stream().cuda_stream)
+            assert rcp == 0
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+
     ms_per_step = elapsed / args.steps * 1e3
     value = N * args.steps / elapsed
     # dominant kernel: the logit sweep.  Algorithmic bytes per launch: every bf16 logit once,
@@ -121,7 +136,7 @@ def main():
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": B, "traj_steps": N,
                    "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
                    "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha},
-        "roofline": {"bound": "hbm", "kernel": "k_score_rows (+ per-step sums)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "k_score_rows (+ k_step_sums inside the same event bracket)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": None, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
     }

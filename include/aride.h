@@ -79,7 +79,7 @@ typedef struct {
  */
 int aride_workspace_bytes(int64_t M, size_t* out_bytes);
 
-/* Clears the status word and the replay index.  Must run once before first use. */
+/* Zeroes the whole workspace (status word, replay index).  Must run once before first use. */
 int aride_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -96,7 +96,8 @@ int aride_status_read(const void* ws, aride_status* out /* host */, void* stream
  *     tok_logp = logp_{tokens[r]},   tok_ent = - sum_v exp(logp_v) logp_v
  * and per step n the sums over its A rows: step_logp[n] = log pi(a_n|s_n) (the
  * numerator of the ratio rho of Section 5.1), step_ent[n] = entropy along the realised
- * token path.  Each logit is read from memory exactly once; accumulation is fp32.
+ * token path.  Each logit is read from memory exactly once; accumulation is fp32 per row
+ * (fp64 for the A-term per-step sums, rounded once).
  *
  *  logits  bf16 [R, row_stride] row-major, device; the first V columns of a row are
  *          used.  Base pointer 16-byte aligned; row_stride >= V.  Rows whose byte
@@ -104,10 +105,12 @@ int aride_status_read(const void* ws, aride_status* out /* host */, void* stream
  *  tokens  int32 [R]; a negative token marks a padding row (contributes 0 to every
  *          output); a token >= V is masked the same way and sets ARIDE_ST_BAD_TOKEN.
  *  tok_logp, tok_ent   fp32 [R], nullable -- except that step_logp needs tok_logp and
- *                      step_ent needs tok_ent (the per-step sums are formed from them).
+ *                      step_ent needs tok_ent: the per-step sums are formed from them by a
+ *                      second, small kernel (fp64 running sums, rounded to fp32 once).
  *  step_logp, step_ent fp32 [R/A], nullable.
  *  ws      workspace (only its status word is used).
- * Errors: E_NULL (logits/tokens, or a per-step output without its per-token array), E_SHAPE (R<0, V<=0, A<=0, R%A!=0, stride<V),
+ * Errors: E_NULL (logits/tokens, or a per-step output without its per-token array), E_SHAPE
+ *         (R<0, V<=0, A<=0, R%A!=0, stride<V),
  *         E_ALIGN, E_RANGE (V > 2^31-1), E_WORKSPACE.  R == 0 is a no-op.
  */
 int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,

@@ -8,6 +8,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaride.so")
 SOURCES = ["api.hip", "score_logits.hip", "retrace.hip", "replay.hip"]
+PROBE_LIB = os.path.join(HERE, "libaride_probe.so")   # counter-calibration copy kernel, not part of the ABI
+PROBE_SOURCES = ["copy_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -20,11 +22,25 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra=None, out: str = LIB) -> str:
-    cmd = ["hipcc"] + FLAGS + (extra or []) + ["-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
+def _compile(sources, out, extra, verbose):
+    cmd = ["hipcc"] + FLAGS + (extra or []) + ["-o", out] + [os.path.join(CSRC, s) for s in sources]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    # the host pass does not know the packed-fp32 target feature and says so once per kernel; harmless
+    res = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    noise = "'-packed-fp32-ops' is not a recognized feature"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if err.strip():
+        print(err, file=sys.stderr, flush=True)
+    if res.returncode != 0:
+        raise subprocess.CalledProcessError(res.returncode, cmd)
+    return out
+
+
+def build(verbose: bool = False, extra=None, out: str = LIB) -> str:
+    _compile(SOURCES, out, extra, verbose)
+    if out == LIB:
+        _compile(PROBE_SOURCES, PROBE_LIB, None, verbose)
     return out
 
 

@@ -5,16 +5,17 @@
 
 namespace aride {
 hipError_t score_logits_launch(const uint16_t*, long long, int, long long, const int*, int, float*,
-                               float*, float*, float*, uint32_t*, int, hipStream_t);
+                               float*, float*, float*, uint32_t*, hipStream_t);
 hipError_t retrace_launch(const float*, const float*, const float*, const float*, const float*,
                           const float*, const int*, int, int, float, float, float*, float*, float*,
                           hipStream_t);
 hipError_t priorities_launch(const float*, const float*, const float*, const int*, int, int, float,
                              float, float, float, float, float, int, float*, float*, hipStream_t);
 hipError_t update_launch(float*, long long, const long long*, const float*, int, float, WsHeader*,
-                         unsigned long long*, hipStream_t);
+                         unsigned long long*, unsigned long long*, uint32_t*, hipStream_t);
 hipError_t sample_launch(const float*, long long, const WsHeader*, const unsigned long long*,
-                         const double*, int, long long*, float*, uint32_t*, hipStream_t);
+                         const unsigned long long*, const double*, int, long long*, float*, uint32_t*,
+                         hipStream_t);
 
 static_assert(sizeof(aride_status) == 24, "status block layout");
 static_assert(sizeof(WsHeader) == sizeof(aride_status), "device header mirrors the status block");
@@ -26,7 +27,7 @@ __global__ void k_fill_u64(unsigned long long* p, size_t n) {
 
 static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline size_t replay_blocks(int64_t M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
-static inline size_t index_bytes(int64_t M) { return round_up(replay_blocks(M) * 8, 256); }
+static inline size_t index_bytes(int64_t M) { return M > 0 ? kSuperBytes + kPartBytes + round_up(replay_blocks(M) * 8, 256) : 0; }
 static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 }  // namespace aride
 
@@ -70,9 +71,10 @@ int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t ro
     if (!logits_bf16 || !tokens) return ARIDE_E_NULL;
     if (misaligned(logits_bf16, 16) || misaligned(tokens, 4)) return ARIDE_E_ALIGN;
     if ((step_logp && !tok_logp) || (step_ent && !tok_ent)) return ARIDE_E_NULL;
+    if (R / A > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
     if (ws_bytes < kHeaderBytes) return ARIDE_E_WORKSPACE;
     hipError_t err = score_logits_launch((const uint16_t*)logits_bf16, R, (int)V, row_stride, tokens, A,
-                                         tok_logp, tok_ent, step_logp, step_ent, (uint32_t*)ws, 0,
+                                         tok_logp, tok_ent, step_logp, step_ent, (uint32_t*)ws,
                                          (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
@@ -124,9 +126,11 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
     if (K > 0 && (!idx || !prio)) return ARIDE_E_NULL;
     if (K > 0 && misaligned(idx, 8)) return ARIDE_E_ALIGN;
     WsHeader* hdr = (WsHeader*)ws;
-    unsigned long long* cum = (unsigned long long*)((char*)ws + kHeaderBytes);
-    hipError_t err = update_launch(weights, M, (const long long*)idx, prio, (int)K, alpha, hdr, cum,
-                                   (hipStream_t)stream);
+    unsigned long long* super_cum = (unsigned long long*)((char*)ws + kHeaderBytes);
+    uint32_t* partial_max = (uint32_t*)((char*)ws + kHeaderBytes + kSuperBytes);
+    unsigned long long* block_cum = (unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
+    hipError_t err = update_launch(weights, M, (const long long*)idx, prio, (int)K, alpha, hdr, block_cum,
+                                   super_cum, partial_max, (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
 
@@ -141,9 +145,11 @@ int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t w
     if (!uniforms || !idx_out) return ARIDE_E_NULL;
     if (misaligned(uniforms, 8) || misaligned(idx_out, 8)) return ARIDE_E_ALIGN;
     const WsHeader* hdr = (const WsHeader*)ws;
-    const unsigned long long* cum = (const unsigned long long*)((char*)ws + kHeaderBytes);
-    hipError_t err = sample_launch(weights, M, hdr, cum, uniforms, (int)K, (long long*)idx_out, prob_out,
-                                   (uint32_t*)ws, (hipStream_t)stream);
+    const unsigned long long* super_cum = (const unsigned long long*)((char*)ws + kHeaderBytes);
+    const unsigned long long* block_cum =
+        (const unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
+    hipError_t err = sample_launch(weights, M, hdr, block_cum, super_cum, uniforms, (int)K,
+                                   (long long*)idx_out, prob_out, (uint32_t*)ws, (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
 

@@ -5,9 +5,12 @@
 // summation order gives the same answer:
 //     e = ilogb(max w) + 1,  q_i = floor(w_i * 2^(39-e)) < 2^39,  C_i = q_0 + ... + q_i (u64)
 //     t = min(floor(u * (double)Total), Total - 1),  idx = min{ i : C_i > t }
-// The index kept in the workspace is the inclusive prefix of the per-block sums of q
-// (blocks of 256 weights = one wave x float4); a draw bisects that prefix and then scans
-// one 1 KB block with a wave-wide integer prefix sum.
+// The index kept in the workspace has two levels: blocks of 256 weights (one wave x float4)
+// and super-blocks of 256 blocks.  block_cum holds, per super-block, the inclusive prefix of
+// its block sums; super_cum holds the inclusive prefix of the super-block totals (padded to
+// 256 entries with Total).  A draw needs three dependent reads: all 256 entries of
+// super_cum at once (4 per lane, counted with ballots), the 256 block prefixes of the chosen
+// super-block the same way, then one 1 KB block of weights with a wave-wide integer scan.
 //
 // update_priorities resolves repeated indices without a serial loop: pass 1 writes the
 // tag (0xFF800000 | k) with an unsigned atomic max into the weight slot itself -- every
@@ -42,14 +45,9 @@ __device__ __forceinline__ int exponent_of(uint32_t wmax_bits) {
     return (31 - __clz(mant)) - 149 + 1;
 }
 
-__global__ void k_reset_index(WsHeader* hdr) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->wmax_bits = 0u; hdr->total = 0ull; hdr->exponent = 0; }
-}
-
 __global__ __launch_bounds__(256) void k_update_tag(
     float* __restrict__ weights, long long M, const long long* __restrict__ idx, int K, WsHeader* hdr) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k == 0) { hdr->wmax_bits = 0u; hdr->total = 0ull; hdr->exponent = 0; }
     if (k >= K) return;
     const long long i = idx[k];
     if (i < 0 || i >= M) { atomicOr(&hdr->flags, 0x8u); return; }
@@ -63,15 +61,21 @@ __global__ __launch_bounds__(256) void k_update_commit(
     if (k >= K) return;
     const long long i = idx[k];
     if (i < 0 || i >= M) return;
-    volatile uint32_t* slot = reinterpret_cast<volatile uint32_t*>(weights) + i;
-    if (*slot != (kTagBase | (uint32_t)k)) return;   // an occurrence later in the batch owns the slot
+    const uint32_t seen = __hip_atomic_load(reinterpret_cast<uint32_t*>(weights) + i, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+    if (seen != (kTagBase | (uint32_t)k)) return;    // an occurrence later in the batch owns the slot
     double p = (double)prio[k];
     if (!(p > 0.0)) p = 0.0;
     weights[i] = (float)pow(p, (double)alpha);
 }
 
-// Pass A of the rebuild: largest valid weight (order-free, exact).
-__global__ __launch_bounds__(256) void k_weight_max(const float* __restrict__ weights, long long M, WsHeader* hdr) {
+// Pass A of the rebuild: largest valid weight (order-free, exact).  Each of the kMaxParts
+// workgroups writes the maximum of its share to partial_max; the consumers reduce those 1024
+// words themselves.  (One atomic per wave onto a single header word was measured at ~160 us
+// for M = 2^24: same-address atomics serialise.)
+__global__ __launch_bounds__(256) void k_weight_max(const float* __restrict__ weights, long long M, WsHeader* hdr,
+                                                    uint32_t* __restrict__ partial_max) {
+    __shared__ uint32_t wave_best[4];
     const long long nvec = M >> 2;
     const float4* wv = reinterpret_cast<const float4*>(weights);
     uint32_t best = 0u;
@@ -90,43 +94,182 @@ __global__ __launch_bounds__(256) void k_weight_max(const float* __restrict__ we
     for (int d = 32; d >= 1; d >>= 1) best = max(best, (uint32_t)__shfl_xor((int)best, d, kWave));
     const bool any_bad = __any(bad);
     if ((threadIdx.x & 63) == 0) {
-        if (best) atomicMax(&hdr->wmax_bits, best);
+        wave_best[threadIdx.x >> 6] = best;
         if (any_bad) atomicOr(&hdr->flags, 0x2u);
     }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial_max[blockIdx.x] = max(max(wave_best[0], wave_best[1]), max(wave_best[2], wave_best[3]));
 }
 
-// Pass B: integer sum of each block of 256 weights (one wave per block).
-__global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ weights, long long M,
-                                                    const WsHeader* __restrict__ hdr,
-                                                    unsigned long long* __restrict__ block_sum, int nblk) {
-    const int lane = threadIdx.x & 63;
-    const int blk = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (blk >= nblk) return;
-    const uint32_t wb = hdr->wmax_bits;
-    unsigned long long s = 0ull;
-    if (wb != 0u) {
-        const int e = exponent_of(wb);
+// Maximum of the kMaxParts partial maxima; every thread of a workgroup of NT threads calls it.
+template <int NT>
+__device__ __forceinline__ uint32_t reduce_partial_max(const uint32_t* __restrict__ partial_max, uint32_t* lds_waves) {
+    uint32_t best = 0u;
+    for (int i = threadIdx.x; i < kMaxParts; i += NT) best = max(best, partial_max[i]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) best = max(best, (uint32_t)__shfl_xor((int)best, d, kWave));
+    if ((threadIdx.x & 63) == 0) lds_waves[threadIdx.x >> 6] = best;
+    __syncthreads();
+    uint32_t wb = 0u;
+#pragma unroll
+    for (int w = 0; w < NT / kWave; ++w) wb = max(wb, lds_waves[w]);
+    return wb;
+}
+
+// Inclusive scan over the first 256 threads (4 waves) of a workgroup.  EVERY thread of the
+// workgroup must call it (it contains a barrier); the result is meaningful for threads < 256.
+__device__ __forceinline__ unsigned long long scan256(unsigned long long v, unsigned long long* wave_tot4,
+                                                      unsigned long long& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        unsigned long long up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63 && wave < 4) wave_tot4[wave] = incl;
+    __syncthreads();
+    unsigned long long before = 0ull;
+    total = 0ull;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { if (w < wave) before += wave_tot4[w]; total += wave_tot4[w]; }
+    return before + incl;
+}
+
+// Pass B: one workgroup of 1024 threads per super-block (65536 weights): each wave sums 16
+// blocks of 256 weights as integers, then the 256 block sums are scanned in LDS.  Writes the
+// within-super-block inclusive prefixes and the super-block's total.
+__global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ weights, long long M,
+                                                     const uint32_t* __restrict__ partial_max,
+                                                     unsigned long long* __restrict__ block_cum, int nblk,
+                                                     unsigned long long* __restrict__ super_raw) {
+    __shared__ unsigned long long sums[kSuperBlocks];
+    __shared__ unsigned long long wave_tot4[4];
+    __shared__ uint32_t wave_best[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sblk = blockIdx.x;
+    const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
+    const int e = wb ? exponent_of(wb) : 0;
+    float4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int blk = sblk * kSuperBlocks + wave * 16 + j;
         const long long base = (long long)blk * kReplayBlock + lane * 4;
-        if (base + 3 < M) {
-            const float4 v = *reinterpret_cast<const float4*>(weights + base);
-            s = quantise(v.x, e) + quantise(v.y, e) + quantise(v.z, e) + quantise(v.w, e);
-        } else {
-            for (int j = 0; j < 4; ++j) if (base + j < M) s += quantise(weights[base + j], e);
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (base + 3 < M) v[j] = *reinterpret_cast<const float4*>(weights + base);
+        else if (base < M) {
+            v[j].x = weights[base];
+            if (base + 1 < M) v[j].y = weights[base + 1];
+            if (base + 2 < M) v[j].z = weights[base + 2];
         }
     }
-    s = wave_sum_u64(s);
-    if (lane == 0) block_sum[blk] = s;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        unsigned long long q = 0ull;
+        if (wb != 0u) q = quantise(v[j].x, e) + quantise(v[j].y, e) + quantise(v[j].z, e) + quantise(v[j].w, e);
+        q = wave_sum_u64(q);
+        if (lane == 0) sums[wave * 16 + j] = q;
+    }
+    __syncthreads();
+    unsigned long long total = 0ull;
+    const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
+    if (tid < kSuperBlocks) {
+        const int blk = sblk * kSuperBlocks + tid;
+        if (blk < nblk) block_cum[blk] = incl;
+        if (tid == 0) super_raw[sblk] = total;
+    }
 }
 
-// Pass C: in-place inclusive prefix over the block sums; one workgroup of 1024 threads,
-// each owning a contiguous run.  Also publishes Total, the exponent and the no-mass flag.
-__global__ __launch_bounds__(1024) void k_prefix_blocks(unsigned long long* __restrict__ block_sum, int nblk, WsHeader* hdr) {
+// Pass C: inclusive prefix of the (at most 256) super-block totals, padded with Total; also
+// publishes Total, the exponent and the no-mass flag.
+__global__ __launch_bounds__(256) void k_prefix_super(unsigned long long* __restrict__ super_cum, int nsuper,
+                                                      const uint32_t* __restrict__ partial_max, WsHeader* hdr) {
+    __shared__ unsigned long long wave_tot4[4];
+    __shared__ uint32_t wave_best[4];
+    const int tid = threadIdx.x;
+    const uint32_t wb = reduce_partial_max<256>(partial_max, wave_best);
+    unsigned long long total = 0ull;
+    const unsigned long long incl = scan256(tid < nsuper ? super_cum[tid] : 0ull, wave_tot4, total);
+    super_cum[tid] = incl;    // entries past nsuper repeat Total
+    if (tid == 0) {
+        hdr->wmax_bits = wb;
+        hdr->total = total;
+        hdr->exponent = wb ? exponent_of(wb) : 0;
+        if (total == 0ull) atomicOr(&hdr->flags, 0x4u);
+    }
+}
+
+// Small buffers (M <= kSmallReplay): the whole update -- tag, commit, maximum, block sums, prefix --
+// in ONE workgroup of 1024 threads, phases separated by workgroup barriers.  Five dependent
+// launches cost more than the work itself at this size; one compute unit stops paying off
+// beyond a few thousand weights (measured: 50 us at M = 65536 against 22 us for five launches).
+constexpr int kSmallReplay = 1 << 13;   // 32 indexed blocks (the scan phase handles up to 1024)
+constexpr int kSmallBatch = 1 << 13;
+
+__global__ __launch_bounds__(1024) void k_update_small(
+    float* __restrict__ weights, int M, const long long* __restrict__ idx, const float* __restrict__ prio,
+    int K, float alpha, WsHeader* hdr, unsigned long long* __restrict__ block_cum, int nblk,
+    unsigned long long* __restrict__ super_cum) {
+    __shared__ unsigned long long sums[1024];
     __shared__ unsigned long long wave_tot[16];
+    __shared__ uint32_t wave_max_bits[16];
+    __shared__ int any_bad;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int per = (nblk + 1023) / 1024;
-    const int lo = min(tid * per, nblk), hi = min(lo + per, nblk);
-    unsigned long long mine = 0ull;
-    for (int i = lo; i < hi; ++i) mine += block_sum[i];
+    uint32_t* wbits = reinterpret_cast<uint32_t*>(weights);
+    if (tid == 0) any_bad = 0;
+
+    // 1. tag: the last occurrence of an index carries the largest tag
+    for (int k = tid; k < K; k += 1024) {
+        const long long i = idx[k];
+        if (i < 0 || i >= M) { atomicOr(&hdr->flags, 0x8u); continue; }
+        atomicMax(wbits + i, kTagBase | (uint32_t)k);
+    }
+    __syncthreads();
+    // 2. commit: exactly the winning k stores its weight
+    for (int k = tid; k < K; k += 1024) {
+        const long long i = idx[k];
+        if (i < 0 || i >= M) continue;
+        const uint32_t seen = __hip_atomic_load(wbits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen != (kTagBase | (uint32_t)k)) continue;
+        double p = (double)prio[k];
+        if (!(p > 0.0)) p = 0.0;
+        __hip_atomic_store(weights + i, (float)pow(p, (double)alpha), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    // 3. largest valid weight
+    uint32_t best = 0u;
+    bool bad = false;
+#pragma unroll 8
+    for (int i = tid; i < M; i += 1024) {
+        const uint32_t b = __hip_atomic_load(wbits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (b < 0x7F800000u) best = max(best, b);
+        else if (b != 0x80000000u) bad = true;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) best = max(best, (uint32_t)__shfl_xor((int)best, d, kWave));
+    if (__any(bad) && lane == 0) any_bad = 1;
+    if (lane == 0) wave_max_bits[wave] = best;
+    __syncthreads();
+    uint32_t wb = 0u;
+    for (int w = 0; w < 16; ++w) wb = max(wb, wave_max_bits[w]);
+    const int e = wb ? exponent_of(wb) : 0;
+    // 4. integer sum of each block of 256 weights, one wave per block
+    for (int blk = wave; blk < nblk; blk += 16) {
+        unsigned long long q = 0ull;
+        if (wb != 0u) {
+            const int base = blk * kReplayBlock + lane * 4;
+            for (int j = 0; j < 4; ++j)
+                if (base + j < M)
+                    q += quantise(bits_to_float(__hip_atomic_load(wbits + base + j, __ATOMIC_RELAXED,
+                                                                  __HIP_MEMORY_SCOPE_AGENT)), e);
+        }
+        q = wave_sum_u64(q);
+        if (lane == 0) sums[blk] = q;
+    }
+    __syncthreads();
+    // 5. inclusive prefix over the (at most 1024) block sums
+    const unsigned long long mine = tid < nblk ? sums[tid] : 0ull;
     unsigned long long incl = mine;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -137,19 +280,29 @@ __global__ __launch_bounds__(1024) void k_prefix_blocks(unsigned long long* __re
     __syncthreads();
     unsigned long long before = 0ull, total = 0ull;
     for (int w = 0; w < 16; ++w) { if (w < wave) before += wave_tot[w]; total += wave_tot[w]; }
-    unsigned long long run = before + incl - mine;
-    for (int i = lo; i < hi; ++i) { run += block_sum[i]; block_sum[i] = run; }
+    if (tid < nblk) block_cum[tid] = before + incl;
+    if (tid < kSuperBlocks) super_cum[tid] = total;   // a single super-block
     if (tid == 0) {
+        hdr->wmax_bits = wb;
         hdr->total = total;
-        hdr->exponent = hdr->wmax_bits ? exponent_of(hdr->wmax_bits) : 0;
-        if (total == 0ull) atomicOr(&hdr->flags, 0x4u);
+        hdr->exponent = e;
+        uint32_t f = (any_bad ? 0x2u : 0u) | (total == 0ull ? 0x4u : 0u);
+        if (f) atomicOr(&hdr->flags, f);
     }
+}
+
+// Number of entries of a non-decreasing run of 256 u64 values that are <= t, i.e. the index of
+// the first entry > t.  Lane l holds entries 4l .. 4l+3.
+__device__ __forceinline__ int count_le(const unsigned long long (&c)[4], unsigned long long t) {
+    return __popcll(__ballot(c[0] <= t)) + __popcll(__ballot(c[1] <= t)) +
+           __popcll(__ballot(c[2] <= t)) + __popcll(__ballot(c[3] <= t));
 }
 
 // One wave per draw.
 __global__ __launch_bounds__(256) void k_sample(
     const float* __restrict__ weights, long long M, const WsHeader* __restrict__ hdr,
-    const unsigned long long* __restrict__ block_cum, int nblk, const double* __restrict__ uniforms,
+    const unsigned long long* __restrict__ block_cum, int nblk,
+    const unsigned long long* __restrict__ super_cum, const double* __restrict__ uniforms,
     int K, long long* __restrict__ idx_out, float* __restrict__ prob_out, uint32_t* __restrict__ flags) {
     const int lane = threadIdx.x & 63;
     const int k = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
@@ -166,15 +319,32 @@ __global__ __launch_bounds__(256) void k_sample(
     unsigned long long t = (prod >= 18446744073709551616.0) ? total - 1 : (unsigned long long)prod;
     if (t > total - 1) t = total - 1;
 
-    // first block whose inclusive prefix exceeds t (block_cum[nblk-1] = Total > t)
-    int lo = 0, hi = nblk - 1;
-    while (lo < hi) {
-        const int mid = lo + ((hi - lo) >> 1);
-        if (block_cum[mid] > t) hi = mid; else lo = mid + 1;
+    // level 1: first super-block whose inclusive prefix exceeds t (the padding equals Total > t)
+    unsigned long long c[4];
+    {
+        const ulonglong2 a = *reinterpret_cast<const ulonglong2*>(super_cum + 4 * lane);
+        const ulonglong2 b = *reinterpret_cast<const ulonglong2*>(super_cum + 4 * lane + 2);
+        c[0] = a.x; c[1] = a.y; c[2] = b.x; c[3] = b.y;
     }
-    const int blk = lo;
-    const unsigned long long rem = t - (blk ? block_cum[blk - 1] : 0ull);
+    const int sblk = count_le(c, t);
+    unsigned long long rem = t - (sblk ? super_cum[sblk - 1] : 0ull);
+    // level 2: first block of that super-block whose inclusive prefix exceeds the remainder
+    const int first = sblk * kSuperBlocks;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int blk = first + 4 * lane + j;
+        c[j] = blk < nblk ? block_cum[blk] : ~0ull;
+    }
+    const int within = count_le(c, rem);
+    const int blk = first + within;
+    // a stale index (weights changed without a rebuild) can run past the end: report -1
+    if (sblk >= kSuperBlocks || within >= kSuperBlocks || blk >= nblk) {
+        if (lane == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
+        return;
+    }
+    rem -= within ? block_cum[blk - 1] : 0ull;
 
+    // level 3: scan the block's 256 weights
     const int e = exponent_of(hdr->wmax_bits);
     const long long base = (long long)blk * kReplayBlock + lane * 4;
     unsigned long long qv[4] = {0ull, 0ull, 0ull, 0ull};
@@ -192,45 +362,49 @@ __global__ __launch_bounds__(256) void k_sample(
         if (lane >= d) incl += up;
     }
     const unsigned long long hit = __ballot(incl > rem);
-    // hit is non-zero when the index matches the weights; a stale index yields -1
-    if (hit == 0ull) {
+    if (hit == 0ull) {   // stale index again
         if (lane == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
         return;
     }
     const int owner = __ffsll((long long)hit) - 1;
     if (lane == owner) {
-        unsigned long long c = incl - mine;
+        unsigned long long cc = incl - mine;
         int j = 0;
-        for (; j < 3; ++j) { if (c + qv[j] > rem) break; c += qv[j]; }
+        for (; j < 3; ++j) { if (cc + qv[j] > rem) break; cc += qv[j]; }
         idx_out[k] = base + j;
         if (prob_out) prob_out[k] = (float)((double)qv[j] / (double)total);
     }
 }
 
 hipError_t update_launch(float* weights, long long M, const long long* idx, const float* prio, int K,
-                         float alpha, WsHeader* hdr, unsigned long long* block_cum, hipStream_t st) {
+                         float alpha, WsHeader* hdr, unsigned long long* block_cum,
+                         unsigned long long* super_cum, uint32_t* partial_max, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
+    const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
+    if (M <= kSmallReplay && K <= kSmallBatch) {
+        hipLaunchKernelGGL(k_update_small, dim3(1), dim3(1024), 0, st, weights, (int)M, idx, prio, K, alpha,
+                           hdr, block_cum, nblk, super_cum);
+        return hipGetLastError();
+    }
     if (K > 0) {
         const unsigned g = (unsigned)((K + 255) / 256);
         hipLaunchKernelGGL(k_update_tag, dim3(g), dim3(256), 0, st, weights, M, idx, K, hdr);
         hipLaunchKernelGGL(k_update_commit, dim3(g), dim3(256), 0, st, weights, M, idx, prio, K, alpha);
-    } else {
-        hipLaunchKernelGGL(k_reset_index, dim3(1), dim3(64), 0, st, hdr);
     }
-    long long want = ((M >> 2) + 255) / 256;
-    unsigned gmax = (unsigned)(want < 1 ? 1 : (want > 4096 ? 4096 : want));
-    hipLaunchKernelGGL(k_weight_max, dim3(gmax), dim3(256), 0, st, weights, M, hdr);
-    hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M, hdr, block_cum, nblk);
-    hipLaunchKernelGGL(k_prefix_blocks, dim3(1), dim3(1024), 0, st, block_cum, nblk, hdr);
+    hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, hdr, partial_max);
+    hipLaunchKernelGGL(k_super_sums, dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, partial_max,
+                       block_cum, nblk, super_cum);
+    hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, super_cum, nsuper, partial_max, hdr);
     return hipGetLastError();
 }
 
 hipError_t sample_launch(const float* weights, long long M, const WsHeader* hdr,
-                         const unsigned long long* block_cum, const double* uniforms, int K,
-                         long long* idx_out, float* prob_out, uint32_t* flags, hipStream_t st) {
+                         const unsigned long long* block_cum, const unsigned long long* super_cum,
+                         const double* uniforms, int K, long long* idx_out, float* prob_out,
+                         uint32_t* flags, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
     const unsigned g = (unsigned)(((long long)K * kWave + 255) / 256);
-    hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, hdr, block_cum, nblk,
+    hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, hdr, block_cum, nblk, super_cum,
                        uniforms, K, idx_out, prob_out, flags);
     return hipGetLastError();
 }

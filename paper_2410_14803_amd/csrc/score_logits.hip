@@ -19,8 +19,18 @@
 
 namespace aride {
 
+// Tuning parameters (the defaults are the measured best on MI355X for V = 32128 .. 151936).
 #ifndef ARIDE_SCORE_WPR
-#define ARIDE_SCORE_WPR 1   // waves per logit row (1, 2 or 4)
+#define ARIDE_SCORE_WPR 1       // waves per logit row (1, 2 or 4)
+#endif
+#ifndef ARIDE_SCORE_UNROLL
+#define ARIDE_SCORE_UNROLL 4    // 16-byte loads in flight per lane and batch
+#endif
+#ifndef ARIDE_SCORE_PIPELINE
+#define ARIDE_SCORE_PIPELINE 0  // 1: issue the next batch of loads before reducing the current one
+#endif
+#ifndef ARIDE_SCORE_NT
+#define ARIDE_SCORE_NT 1        // 1: non-temporal loads
 #endif
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -44,8 +54,8 @@ __device__ __forceinline__ void lane_rebase(LaneState& a, float gm) {
     float d = -a.negk - knew;   // old k - new k  (<= 0, or -inf on first use)
     float r = fast_exp2(d);
     float s = a.s0 + a.s1, t = a.t0 + a.t1;
-    a.t0 = (s > 0.f) ? r * fmaf(d, s, t) : 0.f;
-    a.s0 = (s > 0.f) ? s * r : 0.f;
+    a.t0 = (s != 0.f) ? r * fmaf(d, s, t) : 0.f;
+    a.s0 = (s != 0.f) ? s * r : 0.f;
     a.s1 = 0.f; a.t1 = 0.f;
     a.ref = gm; a.negk = -knew;
 }
@@ -62,7 +72,8 @@ __device__ __forceinline__ void lane_accumulate(LaneState& a, const float (&x)[N
         if constexpr ((NE & 1) == 0) { gm = fmaxf(gm, x[NE - 1]); gn = fminf(gn, x[NE - 1]); }
     }
     a.mx = fmaxf(a.mx, gm);
-    if (gm > a.ref + kWindow) lane_rebase(a, gm);
+    // a reference below kHugeNeg would overflow k = ref*log2e; such logits count as -inf
+    if (gm > a.ref + kWindow) lane_rebase(a, fmaxf(gm, kHugeNeg));
     if (gn > kHugeNeg) {
 #pragma unroll
         for (int j = 0; j < NE; ++j) {
@@ -94,12 +105,28 @@ __device__ __forceinline__ void unpack8(const u32x4& v, float* x) {
     x[6] = bits_to_float(v.w << 16); x[7] = bits_to_float(v.w & 0xffff0000u);
 }
 
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+#if ARIDE_SCORE_NT
+    return __builtin_nontemporal_load(p);   // streamed once: keep it out of the caches' way
+#else
+    return *p;
+#endif
+}
+
+template <int NV>
+__device__ __forceinline__ void accumulate_batch(LaneState& a, const u32x4 (&v)[NV]) {
+    float x[8 * NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) unpack8(v[u], x + 8 * u);
+    lane_accumulate<8 * NV>(a, x);
+}
+
 // Brings a lane's (s, t) from its own reference to the common one: K = kc (log2 units).
 __device__ __forceinline__ void to_common(float negk, float s, float t, float kc, float& so, float& to) {
     float d = -negk - kc;
     float r = fast_exp2(d);
-    so = (s > 0.f) ? s * r : 0.f;
-    to = (s > 0.f) ? r * fmaf(d, s, t) : 0.f;
+    so = (s != 0.f) ? s * r : 0.f;
+    to = (s != 0.f) ? r * fmaf(d, s, t) : 0.f;
 }
 
 template <int WPR, int UNROLL>
@@ -136,20 +163,36 @@ __global__ __launch_bounds__(256) void k_score_rows(
         const u32x4* pv = reinterpret_cast<const u32x4*>(p + head);
 
         int i = l;
-        for (; i + (UNROLL - 1) * kTPR < nvec; i += UNROLL * kTPR) {
+        constexpr int kStride = UNROLL * kTPR;
+#if ARIDE_SCORE_PIPELINE
+        // software pipeline: the next batch of loads is issued before the current one is reduced
+        if (i + (UNROLL - 1) * kTPR < nvec) {
+            u32x4 cur[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) cur[u] = load16(pv + i + u * kTPR);
+            i += kStride;
+            while (i + (UNROLL - 1) * kTPR < nvec) {
+                u32x4 nxt[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) nxt[u] = load16(pv + i + u * kTPR);
+                accumulate_batch<UNROLL>(a, cur);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
+                i += kStride;
+            }
+            accumulate_batch<UNROLL>(a, cur);
+        }
+#else
+        for (; i + (UNROLL - 1) * kTPR < nvec; i += kStride) {
             u32x4 v[UNROLL];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(pv + i + u * kTPR);
-            float x[8 * UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) unpack8(v[u], x + 8 * u);
-            lane_accumulate<8 * UNROLL>(a, x);
+            for (int u = 0; u < UNROLL; ++u) v[u] = load16(pv + i + u * kTPR);
+            accumulate_batch<UNROLL>(a, v);
         }
+#endif
         for (; i < nvec; i += kTPR) {
-            u32x4 v = __builtin_nontemporal_load(pv + i);
-            float x[8];
-            unpack8(v, x);
-            lane_accumulate<8>(a, x);
+            u32x4 v[1] = {load16(pv + i)};
+            accumulate_batch<1>(a, v);
         }
         if (l < head) {
             float x[1] = {bits_to_float(((uint32_t)p[l]) << 16)};
@@ -197,20 +240,34 @@ __global__ __launch_bounds__(256) void k_score_rows(
         if (tok_logp) tok_logp[row] = lp;
         if (tok_ent) tok_ent[row] = en;
     }
+
 }
 
-// Per step: plain sums, in row order, of the step's A per-token values.
+// Per-step sums of the A per-token values: one wave per step, lanes stride over the step's
+// rows (contiguous 4-byte loads), fp64 running sums combined in a fixed butterfly order and
+// rounded to fp32 once.  log pi(a|s) of a long action is a large number whose absolute error
+// passes one-to-one into the relative error of rho, hence the fp64 accumulation.
 __global__ __launch_bounds__(256) void k_step_sums(
     const float* __restrict__ tok_logp, const float* __restrict__ tok_ent, long long N, int A,
     float* __restrict__ step_logp, float* __restrict__ step_ent) {
-    long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= N) return;
-    float sl = 0.f, se = 0.f;
-    const float* pl = tok_logp + n * A;
-    const float* pe = tok_ent + n * A;
-    for (int j = 0; j < A; ++j) { sl += pl[j]; se += pe[j]; }
-    if (step_logp) step_logp[n] = sl;
-    if (step_ent) step_ent[n] = se;
+    const int lane = threadIdx.x & 63;
+    const long long n = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (n >= N) return;   // whole waves leave together
+    double sl = 0.0, se = 0.0;
+    const long long base = n * A;
+    for (int j = lane; j < A; j += kWave) {
+        if (step_logp) sl += (double)tok_logp[base + j];
+        if (step_ent) se += (double)tok_ent[base + j];
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        sl += __shfl_xor(sl, d, kWave);
+        se += __shfl_xor(se, d, kWave);
+    }
+    if (lane == 0) {
+        if (step_logp) step_logp[n] = (float)sl;
+        if (step_ent) step_ent[n] = (float)se;
+    }
 }
 
 template <int WPR, int UNROLL>
@@ -224,26 +281,17 @@ static hipError_t launch_rows(const uint16_t* logits, long long R, int V, long l
     return hipGetLastError();
 }
 
-// wpr: waves per row (1, 2, 4); 0 picks the default.
+// Row sweep, then (when a per-step output is wanted) the per-step sums of the per-token arrays.
 hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long long stride,
                                const int* tokens, int A, float* tok_logp, float* tok_ent,
-                               float* step_logp, float* step_ent, uint32_t* status,
-                               int wpr, hipStream_t st) {
-    hipError_t err;
-    if (wpr == 0) wpr = ARIDE_SCORE_WPR;
-    switch (wpr) {
-        case 4: err = launch_rows<4, 4>(logits, R, V, stride, tokens, tok_logp, tok_ent, status, st); break;
-        case 2: err = launch_rows<2, 4>(logits, R, V, stride, tokens, tok_logp, tok_ent, status, st); break;
-        default: err = launch_rows<1, 4>(logits, R, V, stride, tokens, tok_logp, tok_ent, status, st); break;
-    }
-    if (err != hipSuccess) return err;
-    if (step_logp || step_ent) {
-        long long N = R / A;
-        hipLaunchKernelGGL(k_step_sums, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st,
-                           tok_logp, tok_ent, N, A, step_logp, step_ent);
-        err = hipGetLastError();
-    }
-    return err;
+                               float* step_logp, float* step_ent, uint32_t* status, hipStream_t st) {
+    hipError_t err = launch_rows<ARIDE_SCORE_WPR, ARIDE_SCORE_UNROLL>(logits, R, V, stride, tokens, tok_logp,
+                                                                      tok_ent, status, st);
+    if (err != hipSuccess || (!step_logp && !step_ent)) return err;
+    const long long N = R / A;
+    hipLaunchKernelGGL(k_step_sums, dim3((unsigned)((N * kWave + 255) / 256)), dim3(256), 0, st,
+                       tok_logp, tok_ent, N, A, step_logp, step_ent);
+    return hipGetLastError();
 }
 
 }  // namespace aride

@@ -37,11 +37,12 @@ def test_error_codes_match_header():
 
 
 def test_workspace_bytes(L):
-    assert b.workspace_bytes(0) == 256
-    assert b.workspace_bytes(1) == 512                       # one block sum, rounded to 256
-    assert b.workspace_bytes(256 * 32) == 256 + 256
-    assert b.workspace_bytes(256 * 32 + 1) == 256 + 512
-    assert b.workspace_bytes(1 << 24) == 256 + 8 * 65536
+    assert b.workspace_bytes(0) == 256                       # status block only
+    fixed = 256 + 2048 + 4096                                # status, super-block prefixes, partial maxima
+    assert b.workspace_bytes(1) == fixed + 256               # one block prefix, rounded to 256
+    assert b.workspace_bytes(256 * 32) == fixed + 256
+    assert b.workspace_bytes(256 * 32 + 1) == fixed + 512
+    assert b.workspace_bytes(1 << 24) == fixed + 8 * 65536
     out = ctypes.c_size_t(0)
     assert L.aride_workspace_bytes(-1, ctypes.byref(out)) == b.E_SHAPE
     assert L.aride_workspace_bytes((1 << 24) + 1, ctypes.byref(out)) == b.E_RANGE
@@ -64,6 +65,7 @@ def test_score_logits_rejects_bad_arguments(L):
     assert f(x, 4, 10, 10, t, 1, None, None, None, None, P(4100), 256, None) == b.E_WORKSPACE
     assert f(x, 4, 10, 10, t, 1, None, None, None, None, ws, 100, None) == b.E_WORKSPACE
     assert f(x, 4, 10, 10, t, 1, None, None, P(64), None, ws, 256, None) == b.E_NULL    # step sums need tok arrays
+    assert f(x, 4, 10, 10, t, 1, P(64), None, None, P(64), ws, 256, None) == b.E_NULL
     assert f(x, 0, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.OK         # empty: no-op
 
 

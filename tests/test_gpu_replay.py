@@ -59,8 +59,9 @@ def test_rebuild_and_sample_sizes(oracle, M):
     assert st.wmax == npf(w).max()
 
 
-def test_update_duplicates_last_writer_wins(oracle):
-    M, K = 5000, 3000
+@pytest.mark.parametrize("M", [5000, 20000])      # single-workgroup path and multi-kernel path
+def test_update_duplicates_last_writer_wins(oracle, M):
+    K = 3000
     w = fresh(M, "exp", 7, 0.6, oracle)
     ws = b.Workspace(M)
     g = torch.Generator(device=DEV); g.manual_seed(3)

@@ -158,3 +158,39 @@ def test_config2_full_size_sampled(oracle):
     got, flags = run_gpu(logits, tokens, cfg.A)
     assert flags == 0
     _sampled_rows_check(oracle, cfg, logits, tokens, got, n_rows=200, n_steps=2, seed=12)
+
+
+def test_long_actions(oracle):
+    # A larger than a wave: lanes stride over the step's rows
+    N, A, V = 3, 300, 257
+    logits = synth.logits_bf16(N * A, V, seed=31, device=DEV)
+    tokens = synth.action_tokens(logits, seed=32)
+    got, flags = run_gpu(logits, tokens, A)
+    want = oracle.score_logits(bits_of(logits), npf(tokens), A)
+    compare(got, want, V, A, "A=300")
+    assert flags == 0
+
+
+def test_step_sum_is_the_rounded_exact_sum_of_the_per_token_values():
+    # fp64 accumulation of at most a few hundred fp32 values is exact to well below an fp32 ulp
+    N, A, V = 64, 64, 4000
+    logits = synth.logits_bf16(N * A, V, seed=35, device=DEV, heavy_tail=True)
+    tokens = synth.action_tokens(logits, seed=36)
+    got, _ = run_gpu(logits, tokens, A)
+    exact_lp = got["tok_logp"].astype(np.float64).reshape(N, A).sum(1).astype(np.float32)
+    exact_en = got["tok_ent"].astype(np.float64).reshape(N, A).sum(1).astype(np.float32)
+    np.testing.assert_array_equal(got["step_logp"], exact_lp)
+    np.testing.assert_array_equal(got["step_ent"], exact_en)
+
+
+def test_nonfinite_values_propagate():
+    V, A = 600, 4
+    x = torch.randn(8, V, device=DEV)
+    x[1, 5] = float("-inf")      # the chosen token is a masked vocabulary entry
+    x[6, 9] = float("nan")       # a NaN logit poisons its row
+    logits = x.to(torch.bfloat16)
+    tokens = torch.tensor([0, 5, 2, 3, 4, 5, 6, 7], dtype=torch.int32, device=DEV)
+    got, flags = run_gpu(logits, tokens, A)
+    assert got["tok_logp"][1] == -np.inf and np.isnan(got["tok_logp"][6])
+    assert got["step_logp"][0] == -np.inf and np.isnan(got["step_logp"][1])
+    assert np.isfinite(got["tok_ent"][1]) and np.isnan(got["step_ent"][1])
