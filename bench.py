@@ -24,6 +24,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+# HBM bytes per launch of the logit sweep from hardware counters (profiles/k_score_rows_learner_batch.md):
+# FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
+# plain 1 GiB copy kernel.  Valid only for the kernel source it was measured on (first 16 hex
+# digits of its sha256) and for the learner-batch workload; reported as null otherwise.
+TRAFFIC = {"source_sha256": "f1a5fc72d682b032", "config": 1, "logit_rows": 82144,
+           "bytes_per_launch": 5282333661}
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 
@@ -126,6 +133,11 @@ def main():
     # dominant kernel: the logit sweep.  Algorithmic bytes per launch: every bf16 logit once,
     # one int32 token per row, two fp32 results per row.
     sweep_ms = sum(a.elapsed_time(c) for a, c in events) / args.steps
+    import hashlib
+    src = os.path.join(ROOT, "paper_2410_14803_amd", "csrc", "score_logits.hip")
+    same_kernel = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == TRAFFIC["source_sha256"]
+    traffic = TRAFFIC["bytes_per_launch"] if (same_kernel and args.config == TRAFFIC["config"]
+                                              and R == TRAFFIC["logit_rows"]) else None
     alg_bytes = R * cfg.V * 2 + R * 4 + R * 8
     achieved = alg_bytes / (sweep_ms * 1e-3) / 1e9
     out = {
@@ -138,7 +150,7 @@ def main():
                    "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha},
         "roofline": {"bound": "hbm", "kernel": "k_score_rows (+ k_step_sums inside the same event bracket)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
+                     "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
     }
 
     if not args.no_cpu_baseline:

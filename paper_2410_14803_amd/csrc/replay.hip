@@ -181,6 +181,42 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
     }
 }
 
+// Pass B for buffers of few super-blocks, where one workgroup per super-block would leave the
+// chip idle: integer sum of each block of 256 weights, one wave per block, raw sums to block_cum.
+__global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ weights, long long M,
+                                                    const uint32_t* __restrict__ partial_max,
+                                                    unsigned long long* __restrict__ block_cum, int nblk) {
+    __shared__ uint32_t wave_best[4];
+    const int lane = threadIdx.x & 63;
+    const int blk = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    const uint32_t wb = reduce_partial_max<256>(partial_max, wave_best);
+    if (blk >= nblk) return;
+    unsigned long long q = 0ull;
+    if (wb != 0u) {
+        const int e = exponent_of(wb);
+        const long long base = (long long)blk * kReplayBlock + lane * 4;
+        if (base + 3 < M) {
+            const float4 v = *reinterpret_cast<const float4*>(weights + base);
+            q = quantise(v.x, e) + quantise(v.y, e) + quantise(v.z, e) + quantise(v.w, e);
+        } else {
+            for (int j = 0; j < 4; ++j) if (base + j < M) q += quantise(weights[base + j], e);
+        }
+    }
+    q = wave_sum_u64(q);
+    if (lane == 0) block_cum[blk] = q;
+}
+
+// ... followed by the in-place inclusive scan of each super-block's 256 raw block sums.
+__global__ __launch_bounds__(256) void k_scan_supers(unsigned long long* __restrict__ block_cum, int nblk,
+                                                     unsigned long long* __restrict__ super_raw) {
+    __shared__ unsigned long long wave_tot4[4];
+    const int blk = blockIdx.x * kSuperBlocks + threadIdx.x;
+    unsigned long long total = 0ull;
+    const unsigned long long incl = scan256(blk < nblk ? block_cum[blk] : 0ull, wave_tot4, total);
+    if (blk < nblk) block_cum[blk] = incl;
+    if (threadIdx.x == 0) super_raw[blockIdx.x] = total;
+}
+
 // Pass C: inclusive prefix of the (at most 256) super-block totals, padded with Total; also
 // publishes Total, the exponent and the no-mass flag.
 __global__ __launch_bounds__(256) void k_prefix_super(unsigned long long* __restrict__ super_cum, int nsuper,
@@ -206,6 +242,7 @@ __global__ __launch_bounds__(256) void k_prefix_super(unsigned long long* __rest
 // beyond a few thousand weights (measured: 50 us at M = 65536 against 22 us for five launches).
 constexpr int kSmallReplay = 1 << 13;   // 32 indexed blocks (the scan phase handles up to 1024)
 constexpr int kSmallBatch = 1 << 13;
+constexpr int kFusedSuperMin = 64;      // from this many super-blocks on, one workgroup per super-block
 
 __global__ __launch_bounds__(1024) void k_update_small(
     float* __restrict__ weights, int M, const long long* __restrict__ idx, const float* __restrict__ prio,
@@ -392,8 +429,14 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
         hipLaunchKernelGGL(k_update_commit, dim3(g), dim3(256), 0, st, weights, M, idx, prio, K, alpha);
     }
     hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, hdr, partial_max);
-    hipLaunchKernelGGL(k_super_sums, dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, partial_max,
-                       block_cum, nblk, super_cum);
+    if (nsuper >= kFusedSuperMin) {
+        hipLaunchKernelGGL(k_super_sums, dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, partial_max,
+                           block_cum, nblk, super_cum);
+    } else {
+        hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M,
+                           partial_max, block_cum, nblk);
+        hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, block_cum, nblk, super_cum);
+    }
     hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, super_cum, nsuper, partial_max, hdr);
     return hipGetLastError();
 }
