@@ -335,7 +335,9 @@ __device__ __forceinline__ int count_le(const unsigned long long (&c)[4], unsign
            __popcll(__ballot(c[2] <= t)) + __popcll(__ballot(c[3] <= t));
 }
 
-// One wave per draw.
+// One wave per draw.  (Serving four draws per wave level by level, to overlap their dependent
+// reads, was measured at twice the time: the kernel is bound by instruction issue -- the u64
+// shuffle scan and the quantisation -- not by latency.)
 __global__ __launch_bounds__(256) void k_sample(
     const float* __restrict__ weights, long long M, const WsHeader* __restrict__ hdr,
     const unsigned long long* __restrict__ block_cum, int nblk,
