@@ -53,6 +53,10 @@ def _load():
     lib.oracle_sample_prioritized.restype = ctypes.c_int
     lib.oracle_sample_prioritized.argtypes = [_c_fp, ctypes.c_int64, _c_dp, ctypes.c_int64,
                                               _c_i64p, _c_dp]
+    lib.oracle_actor_loss_grad.restype = ctypes.c_int
+    lib.oracle_actor_loss_grad.argtypes = [_c_u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _c_i32p,
+                                           ctypes.c_int32, _c_dp, _c_dp, _c_dp, _c_dp, ctypes.c_double,
+                                           ctypes.c_double, ctypes.c_double, _c_dp, _c_dp]
     _lib = lib
     return lib
 
@@ -156,3 +160,22 @@ def sample_prioritized(weights, uniforms):
     if rc not in (0, -5):
         raise ValueError(f"oracle_sample_prioritized rc={rc}")
     return idx, prob, rc
+
+
+def actor_loss_grad(logits_bits, tokens, A, rho, target, baseline, beta, scale, penalty=None,
+                    lambda_pen=0.0, V=None, want_grad=True):
+    """Returns (loss, grad[R, V] fp64 or None)."""
+    lib = _load()
+    lb = np.ascontiguousarray(np.asarray(logits_bits, dtype=np.uint16))
+    R, stride = lb.shape
+    V = stride if V is None else int(V)
+    tok = np.ascontiguousarray(np.asarray(tokens, dtype=np.int32))
+    r_, t_, b_, p_ = _f64(rho), _f64(target), _f64(baseline), _f64(penalty)
+    grad = np.zeros((R, V)) if want_grad else None
+    loss = np.zeros(1)
+    rc = lib.oracle_actor_loss_grad(_ptr(lb, _c_u16p), R, V, stride, _ptr(tok, _c_i32p), A, _ptr(r_, _c_dp),
+                                    _ptr(t_, _c_dp), _ptr(b_, _c_dp), _ptr(p_, _c_dp), float(beta),
+                                    float(lambda_pen), float(scale), _ptr(grad, _c_dp), _ptr(loss, _c_dp))
+    if rc != 0:
+        raise ValueError(f"oracle_actor_loss_grad rc={rc}")
+    return float(loss[0]), grad

@@ -239,3 +239,66 @@ int oracle_sample_prioritized(const float* weights, int64_t M, const double* uni
     free(C);
     return 0;
 }
+
+/*
+ * Actor loss of Section 5.1, eq. (1), and its gradient with respect to the logits
+ * (Appendix A.4.2, "Policy Update Mechanism"), for a token-level policy:
+ *   L = scale * sum_t [ - rho_t * A_t * log pi(a_t|s_t) - beta * H_t + lambda_pen * P_t ]
+ * with log pi(a_t|s_t) and H_t the per-step sums of oracle_score_logits, A_t = target_t -
+ * baseline_t the Retrace-corrected advantage (Section 5.2), rho_t and A_t constants of the
+ * differentiation (importance weight and advantage estimate), and P_t the invalid-action
+ * indicator supplied from outside (it does not depend on the logits).  `scale` is 1/N for the
+ * batch mean that stands for the expectation over mu.  For row r of step t, with
+ * p = softmax(x_r):
+ *   dL/dx_{r,v} = scale * [ - rho_t A_t (1[v = tok_r] - p_v) + beta * p_v (log p_v + H_r) ]
+ * (the second term is -beta * dH_r/dx_v).  Masked rows (token < 0 or >= V) get a zero
+ * gradient.  grad is dense [R, V] fp64.
+ */
+int oracle_actor_loss_grad(const uint16_t* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                           const int32_t* tokens, int32_t A, const double* rho,
+                           const double* target, const double* baseline, const double* penalty,
+                           double beta, double lambda_pen, double scale, double* grad,
+                           double* loss_out) {
+    if (R < 0 || V <= 0 || A <= 0 || R % A != 0 || row_stride < V) return -2;
+    int64_t N = R / A;
+    double loss = 0.0;
+    double* logp = (double*)malloc(sizeof(double) * (size_t)V);
+    for (int64_t t = 0; t < N; ++t) {
+        double coef = rho[t] * (target[t] - baseline[t]);
+        double step_logp = 0.0, step_ent = 0.0;
+        for (int32_t j = 0; j < A; ++j) {
+            int64_t r = t * A + j;
+            const uint16_t* row = logits_bf16 + r * row_stride;
+            int32_t tok = tokens[r];
+            if (tok < 0 || tok >= V) {
+                if (grad) for (int64_t v = 0; v < V; ++v) grad[r * V + v] = 0.0;
+                continue;
+            }
+            double m = -INFINITY;
+            for (int64_t v = 0; v < V; ++v) { double x = bf16_to_double(row[v]); if (x > m) m = x; }
+            double sum = 0.0;
+            for (int64_t v = 0; v < V; ++v) sum += exp(bf16_to_double(row[v]) - m);
+            double L = m + log(sum);
+            double ent = 0.0;
+            for (int64_t v = 0; v < V; ++v) {
+                logp[v] = bf16_to_double(row[v]) - L;
+                double p = exp(logp[v]);
+                if (p > 0.0) ent -= p * logp[v];
+            }
+            step_logp += logp[tok];
+            step_ent += ent;
+            if (grad) {
+                for (int64_t v = 0; v < V; ++v) {
+                    double p = exp(logp[v]);
+                    double onehot = (v == tok) ? 1.0 : 0.0;
+                    double ent_term = (p > 0.0) ? p * (logp[v] + ent) : 0.0;
+                    grad[r * V + v] = scale * (-coef * (onehot - p) + beta * ent_term);
+                }
+            }
+        }
+        loss += -coef * step_logp - beta * step_ent + (penalty ? lambda_pen * penalty[t] : 0.0);
+    }
+    free(logp);
+    if (loss_out) *loss_out = scale * loss;
+    return 0;
+}
