@@ -34,6 +34,44 @@ TRAFFIC = {"source_sha256": "f1a5fc72d682b032", "config": 1, "logit_rows": 82144
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 
+def bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, step_logp, step_ent, si, N, R):
+    """One step = one aride_actor_loss_grad call (bf16 gradient + scalar loss) on the batch."""
+    dev = logits.device
+    g = torch.Generator(device=dev); g.manual_seed(99)
+    rho = torch.exp(0.3 * torch.randn(N, generator=g, device=dev))
+    target = torch.rand(N, generator=g, device=dev)
+    grad = torch.empty_like(logits)
+    loss = torch.zeros(1, device=dev)
+
+    def step():
+        b.actor_loss_grad(logits, tokens, cfg.A, tok_logp, tok_ent, step_logp, step_ent, rho, target, si["value"],
+                          0.01, 1.0 / N, grad=grad, loss=loss)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / args.steps
+    alg_bytes = R * cfg.V * 4 + R * 12 + N * 12     # logits in, bf16 gradient out, per-row and per-step scalars
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "trajectory-steps/sec through the actor loss + logit gradient (eq. 1) + % peak HBM GB/s",
+        "value": N * args.steps / elapsed, "unit": "trajectory-steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} (config {cfg.index}), actor_grad path", "traj_steps": N,
+                   "logit_rows": R, "vocab": cfg.V, "grad_dtype": "bf16"},
+        "roofline": {"bound": "hbm", "kernel": "k_actor_grad (+ k_actor_loss)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +80,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = learner batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the CPU sample")
+    ap.add_argument("--path", choices=["scoring", "actor_grad"], default="scoring",
+                    help="scoring: the five-call hot path (default). actor_grad: the actor loss and its logit "
+                         "gradient (eq. (1)), the second sweep over the same logits")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()
@@ -86,6 +127,9 @@ def main():
     uni = synth.uniforms(K * total_iters, seed + 6, dev).view(total_iters, K)
     prio_src = (torch.arange(K, device=dev) % N)   # first K step priorities, wrapping if N < K
     torch.cuda.synchronize()
+
+    if args.path == "actor_grad":
+        return bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, step_logp, step_ent, si, N, R)
 
     def one_step(i, ev=None):
         if ev is not None:

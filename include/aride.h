@@ -65,6 +65,13 @@ typedef struct {
 } aride_prio_cfg;
 
 typedef struct {
+    float beta;        /* entropy weight of eq. (1) */
+    float lambda_pen;  /* weight of the invalid-action penalty of eq. (1) */
+    float scale;       /* multiplies loss and gradient; 1/N for the batch mean */
+    int32_t grad_f32;  /* 0: gradient stored as bf16 (round to nearest even); nonzero: fp32 */
+} aride_actor_cfg;
+
+typedef struct {
     uint32_t flags;     /* OR of ARIDE_ST_* since the last aride_workspace_init */
     uint32_t reserved;
     uint64_t total;     /* integer mass of the replay CDF after the last rebuild */
@@ -196,6 +203,32 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
 int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t ws_bytes,
                              const double* uniforms, int64_t K, int64_t* idx_out,
                              float* prob_out, void* stream);
+
+/*
+ * actor_loss_grad -- Section 5.1, eq. (1) and the policy update of Appendix A.4.2: the actor
+ * loss of a batch and its gradient with respect to the logits, as a second sweep over the
+ * logits that aride_score_logits reduced.  With A_t = target[t] - baseline[t] (the
+ * Retrace-corrected advantage of Sections 5.1/5.2), rho_t and A_t held constant, and
+ * p = softmax of row r of step t:
+ *     loss = scale * sum_t [ -rho_t A_t step_logp[t] - beta step_ent[t] + lambda_pen penalty[t] ]
+ *     grad[r, v] = scale * [ -rho_t A_t (1[v = tokens[r]] - p_v) + beta p_v (log p_v + H_r) ]
+ * Masked rows (token < 0 or >= V) get zeros; columns >= V of a row are left untouched.
+ *
+ *  logits, tokens, R, V, row_stride, A   as for aride_score_logits (same buffers).
+ *  tok_logp, tok_ent    fp32 [R]: the per-token outputs of aride_score_logits on these logits
+ *                       (they supply each row's log-partition function and entropy).
+ *  step_logp, step_ent  fp32 [R/A]: its per-step outputs (needed only for `loss`).
+ *  rho, target, baseline fp32 [R/A]; penalty fp32 [R/A] nullable (invalid-action indicator).
+ *  grad    [R, row_stride] in the logits' layout, bf16 or fp32 per cfg.grad_f32, 16-byte
+ *          aligned, nullable.   loss  fp32 [1] device, nullable.
+ * Errors: E_NULL, E_SHAPE, E_ALIGN, E_RANGE as for aride_score_logits.  R == 0 writes loss = 0.
+ */
+int aride_actor_loss_grad(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                          const int32_t* tokens, int32_t A, const float* tok_logp,
+                          const float* tok_ent, const float* step_logp, const float* step_ent,
+                          const float* rho, const float* target, const float* baseline,
+                          const float* penalty, aride_actor_cfg cfg, void* grad, float* loss,
+                          void* stream);
 
 #ifdef __cplusplus
 }

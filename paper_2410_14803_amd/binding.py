@@ -21,7 +21,7 @@ MAX_REPLAY = 1 << 24
 
 EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
            "aride_score_logits", "aride_retrace_targets", "aride_compute_priorities",
-           "aride_update_priorities", "aride_sample_prioritized"]
+           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad"]
 
 
 class RetraceCfg(ctypes.Structure):
@@ -32,6 +32,11 @@ class PrioCfg(ctypes.Structure):
     _fields_ = [("w_td", ctypes.c_float), ("w_rho", ctypes.c_float), ("w_ent", ctypes.c_float),
                 ("td_scale", ctypes.c_float), ("ent_scale", ctypes.c_float), ("eps", ctypes.c_float),
                 ("truncate_rho", ctypes.c_int32)]
+
+
+class ActorCfg(ctypes.Structure):
+    _fields_ = [("beta", ctypes.c_float), ("lambda_pen", ctypes.c_float), ("scale", ctypes.c_float),
+                ("grad_f32", ctypes.c_int32)]
 
 
 class Status(ctypes.Structure):
@@ -70,6 +75,8 @@ def lib():
     L.aride_update_priorities.argtypes = [vp, i64, vp, vp, i64, f32, vp, sz, vp]
     L.aride_sample_prioritized.restype = ctypes.c_int
     L.aride_sample_prioritized.argtypes = [vp, i64, vp, sz, vp, i64, vp, vp, vp]
+    L.aride_actor_loss_grad.restype = ctypes.c_int
+    L.aride_actor_loss_grad.argtypes = [vp, i64, i64, i64, vp, i32] + [vp] * 8 + [ActorCfg, vp, vp, vp]
     _lib = L
     return L
 
@@ -168,3 +175,22 @@ def sample_prioritized(weights, uniforms, ws, idx_out, prob_out=None):
                                         _p(uniforms, torch.float64), uniforms.numel(),
                                         _p(idx_out, torch.int64), _p(prob_out, torch.float32), _stream())
     _check("aride_sample_prioritized", rc)
+
+
+def actor_loss_grad(logits, tokens, A, tok_logp, tok_ent, step_logp, step_ent, rho, target, baseline,
+                    beta, scale, penalty=None, lambda_pen=0.0, grad=None, loss=None, V=None):
+    """grad: bf16 or fp32 tensor shaped like logits (or None); loss: fp32 tensor [1] (or None)."""
+    assert logits.dtype == torch.bfloat16 and logits.dim() == 2
+    R, stride = logits.shape
+    V = stride if V is None else int(V)
+    f = torch.float32
+    grad_f32 = 0
+    if grad is not None:
+        assert grad.shape == logits.shape and grad.dtype in (torch.bfloat16, torch.float32)
+        grad_f32 = int(grad.dtype == torch.float32)
+    cfg = ActorCfg(float(beta), float(lambda_pen), float(scale), grad_f32)
+    rc = lib().aride_actor_loss_grad(_p(logits), R, V, stride, _p(tokens, torch.int32), int(A), _p(tok_logp, f),
+                                     _p(tok_ent, f), _p(step_logp, f), _p(step_ent, f), _p(rho, f),
+                                     _p(target, f), _p(baseline, f), _p(penalty, f), cfg, _p(grad),
+                                     _p(loss, f), _stream())
+    _check("aride_actor_loss_grad", rc)

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaride.so")
-SOURCES = ["api.hip", "score_logits.hip", "retrace.hip", "replay.hip"]
+SOURCES = ["api.hip", "score_logits.hip", "retrace.hip", "replay.hip", "actor_grad.hip"]
 PROBE_LIB = os.path.join(HERE, "libaride_probe.so")   # counter-calibration copy kernel, not part of the ABI
 PROBE_SOURCES = ["copy_probe.hip"]
 

@@ -1,0 +1,188 @@
+// actor_loss_grad: the actor loss of Section 5.1, eq. (1) of the DistRL paper and its gradient
+// with respect to the logits (Appendix A.4.2, policy update), as a second sweep over the
+// same bf16 logits that score_logits reduced:
+//   dL/dx_{r,v} = scale * [ -rho_t A_t (1[v = tok_r] - p_v) + beta * p_v (log p_v + H_r) ]
+// The row's log-partition function and entropy are not recomputed: log Z_r = x_tok - tok_logp[r]
+// and H_r = tok_ent[r] come from the first sweep, so each logit is read once and each
+// gradient element written once (4 bytes of HBM traffic per element for bf16 output).
+// One wave per row, 16-byte non-temporal loads and stores; HBM-bound, no MFMA.
+#include "aride_device.h"
+
+namespace aride {
+
+#ifndef ARIDE_ACTOR_NT_STORE
+#define ARIDE_ACTOR_NT_STORE 1  // non-temporal stores for the gradient
+#endif
+#ifndef ARIDE_ACTOR_UNROLL
+#define ARIDE_ACTOR_UNROLL 4   // 16-byte loads in flight per lane
+#endif
+
+constexpr float kLog2eA = 1.4426950408889634f;
+constexpr float kLn2A = 0.6931471805599453f;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+struct RowCoef {
+    float negkz;  // -(log Z) * log2e
+    float cbl;    // scale * beta * ln2
+    float k1;     // coef + scale * beta * H
+    float coef;   // scale * rho * A
+};
+
+__device__ __forceinline__ float grad_of(float x, const RowCoef& c) {
+    // y = log2 p; clamped so that p = 0 multiplies a finite factor (x may be -inf)
+    const float y = fmaxf(fmaf(x, kLog2eA, c.negkz), -200.f);
+    const float p = fast_exp2(y);
+    return p * fmaf(c.cbl, y, c.k1);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);   // round to nearest even
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+__device__ __forceinline__ uint16_t pack_bf16_one(float v) {
+    return (uint16_t)(pack_bf16(v, 0.f) & 0xffffu);
+}
+
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void k_actor_grad(
+    const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
+    const int* __restrict__ tokens, int A, const float* __restrict__ tok_logp,
+    const float* __restrict__ tok_ent, const float* __restrict__ rho, const float* __restrict__ target,
+    const float* __restrict__ baseline, float beta, float scale, void* __restrict__ grad_out) {
+    const int lane = threadIdx.x & 63;
+    const long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (row >= R) return;   // whole waves leave together
+    const int tok = tokens[row];
+    const bool live = tok >= 0 && tok < V;
+    const uint16_t* p = logits + row * row_stride;
+    uint16_t* gb = reinterpret_cast<uint16_t*>(grad_out) + row * row_stride;
+    float* gf = reinterpret_cast<float*>(grad_out) + row * row_stride;
+
+    int head = (int)(((16u - (uint32_t)((uintptr_t)p & 15u)) & 15u) >> 1);
+    if (head > V) head = V;
+    const int nvec = (V - head) >> 3;
+    const int tail0 = head + (nvec << 3);
+
+    RowCoef c;
+    c.negkz = 0.f; c.cbl = 0.f; c.k1 = 0.f; c.coef = 0.f;
+    if (live) {
+        const long long t = row / A;
+        const float xtok = bits_to_float(((uint32_t)p[tok]) << 16);
+        const float logz = xtok - tok_logp[row];
+        c.coef = scale * rho[t] * (target[t] - baseline[t]);
+        const float cb = scale * beta;
+        c.negkz = -logz * kLog2eA;
+        c.cbl = cb * kLn2A;
+        c.k1 = fmaf(cb, tok_ent[row], c.coef);
+    }
+    const int tvec = (live && tok >= head && tok < tail0) ? ((tok - head) >> 3) : -1;
+    const int tsub = (tok - head) & 7;
+
+    const u32x4* pv = reinterpret_cast<const u32x4*>(p + head);
+    auto emit = [&](int i, const u32x4& v) {
+        float g[8];
+        if (live) {
+            g[0] = grad_of(bits_to_float(v.x << 16), c); g[1] = grad_of(bits_to_float(v.x & 0xffff0000u), c);
+            g[2] = grad_of(bits_to_float(v.y << 16), c); g[3] = grad_of(bits_to_float(v.y & 0xffff0000u), c);
+            g[4] = grad_of(bits_to_float(v.z << 16), c); g[5] = grad_of(bits_to_float(v.z & 0xffff0000u), c);
+            g[6] = grad_of(bits_to_float(v.w << 16), c); g[7] = grad_of(bits_to_float(v.w & 0xffff0000u), c);
+            if (i == tvec) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) g[j] -= (j == tsub) ? c.coef : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) g[j] = 0.f;
+        }
+        if constexpr (OUT_F32) {
+            f32x4* o = reinterpret_cast<f32x4*>(gf + head) + 2 * (long long)i;
+            f32x4 a = {g[0], g[1], g[2], g[3]}, b = {g[4], g[5], g[6], g[7]};
+            __builtin_nontemporal_store(a, o);
+            __builtin_nontemporal_store(b, o + 1);
+        } else {
+            u32x4 o = {pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3]), pack_bf16(g[4], g[5]), pack_bf16(g[6], g[7])};
+#if ARIDE_ACTOR_NT_STORE
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(gb + head) + i);
+#else
+            *(reinterpret_cast<u32x4*>(gb + head) + i) = o;
+#endif
+        }
+    };
+    constexpr int kU = ARIDE_ACTOR_UNROLL;
+    int i = lane;
+    if (live) {
+        for (; i + (kU - 1) * kWave < nvec; i += kU * kWave) {
+            u32x4 v[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) v[u] = __builtin_nontemporal_load(pv + i + u * kWave);
+#pragma unroll
+            for (int u = 0; u < kU; ++u) emit(i + u * kWave, v[u]);
+        }
+        for (; i < nvec; i += kWave) emit(i, __builtin_nontemporal_load(pv + i));
+    } else {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (; i < nvec; i += kWave) emit(i, zero);
+    }
+    // elements before the first 16-byte boundary and after the last full vector
+    for (int k = lane; k < head + (V - tail0); k += kWave) {
+        const int v = k < head ? k : tail0 + (k - head);
+        float g = 0.f;
+        if (live) {
+            g = grad_of(bits_to_float(((uint32_t)p[v]) << 16), c);
+            if (v == tok) g -= c.coef;
+        }
+        if constexpr (OUT_F32) gf[v] = g; else gb[v] = pack_bf16_one(g);
+    }
+}
+
+// L = scale * sum_t [ -rho_t A_t log pi(a_t|s_t) - beta H_t + lambda_pen P_t ]: one workgroup,
+// fp64 partial sums combined in a fixed order, one rounding to fp32.
+__global__ __launch_bounds__(1024) void k_actor_loss(
+    const float* __restrict__ step_logp, const float* __restrict__ step_ent, const float* __restrict__ rho,
+    const float* __restrict__ target, const float* __restrict__ baseline, const float* __restrict__ penalty,
+    int N, float beta, float lambda_pen, float scale, float* __restrict__ loss) {
+    __shared__ double wave_part[16];
+    double acc = 0.0;
+    for (int t = threadIdx.x; t < N; t += 1024) {
+        const double coef = (double)rho[t] * ((double)target[t] - (double)baseline[t]);
+        acc += -coef * (double)step_logp[t] - (double)beta * (double)step_ent[t] +
+               (penalty ? (double)lambda_pen * (double)penalty[t] : 0.0);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, kWave);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot = 0.0;
+        for (int w = 0; w < 16; ++w) tot += wave_part[w];
+        *loss = (float)((double)scale * tot);
+    }
+}
+
+hipError_t actor_launch(const uint16_t* logits, long long R, int V, long long stride, const int* tokens,
+                        int A, const float* tok_logp, const float* tok_ent, const float* step_logp,
+                        const float* step_ent, const float* rho, const float* target,
+                        const float* baseline, const float* penalty, float beta, float lambda_pen,
+                        float scale, int grad_f32, void* grad, float* loss, hipStream_t st) {
+    if (grad && R > 0) {
+        const unsigned blocks = (unsigned)((R + 3) / 4);
+        if (grad_f32)
+            hipLaunchKernelGGL((k_actor_grad<true>), dim3(blocks), dim3(256), 0, st, logits, R, V, stride, tokens,
+                               A, tok_logp, tok_ent, rho, target, baseline, beta, scale, grad);
+        else
+            hipLaunchKernelGGL((k_actor_grad<false>), dim3(blocks), dim3(256), 0, st, logits, R, V, stride, tokens,
+                               A, tok_logp, tok_ent, rho, target, baseline, beta, scale, grad);
+    }
+    if (loss)
+        hipLaunchKernelGGL(k_actor_loss, dim3(1), dim3(1024), 0, st, step_logp, step_ent, rho, target, baseline,
+                           penalty, (int)(R / A), beta, lambda_pen, scale, loss);
+    return hipGetLastError();
+}
+
+}  // namespace aride

@@ -17,6 +17,10 @@ hipError_t sample_launch(const float*, long long, const WsHeader*, const unsigne
                          const unsigned long long*, const double*, int, long long*, float*, uint32_t*,
                          hipStream_t);
 
+hipError_t actor_launch(const uint16_t*, long long, int, long long, const int*, int, const float*, const float*,
+                        const float*, const float*, const float*, const float*, const float*, const float*,
+                        float, float, float, int, void*, float*, hipStream_t);
+
 static_assert(sizeof(aride_status) == 24, "status block layout");
 static_assert(sizeof(WsHeader) == sizeof(aride_status), "device header mirrors the status block");
 
@@ -150,6 +154,27 @@ int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t w
         (const unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
     hipError_t err = sample_launch(weights, M, hdr, block_cum, super_cum, uniforms, (int)K,
                                    (long long*)idx_out, prob_out, (uint32_t*)ws, (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_actor_loss_grad(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                          const int32_t* tokens, int32_t A, const float* tok_logp, const float* tok_ent,
+                          const float* step_logp, const float* step_ent, const float* rho,
+                          const float* target, const float* baseline, const float* penalty,
+                          aride_actor_cfg cfg, void* grad, float* loss, void* stream) {
+    if (R < 0 || V <= 0 || A <= 0 || row_stride < V || R % A != 0) return ARIDE_E_SHAPE;
+    if (V > 0x7fffffffLL || R > (int64_t)1 << 40 || R / A > 0x7fffffffLL) return ARIDE_E_RANGE;
+    if (!grad && !loss) return ARIDE_OK;
+    if (R > 0) {
+        if (!rho || !target || !baseline) return ARIDE_E_NULL;
+        if (grad && (!logits_bf16 || !tokens || !tok_logp || !tok_ent)) return ARIDE_E_NULL;
+        if (loss && (!step_logp || !step_ent)) return ARIDE_E_NULL;
+        if (grad && (misaligned(logits_bf16, 16) || misaligned(grad, 16) || misaligned(tokens, 4)))
+            return ARIDE_E_ALIGN;
+    }
+    hipError_t err = actor_launch((const uint16_t*)logits_bf16, R, (int)V, row_stride, tokens, A, tok_logp,
+                                  tok_ent, step_logp, step_ent, rho, target, baseline, penalty, cfg.beta,
+                                  cfg.lambda_pen, cfg.scale, cfg.grad_f32, grad, loss, (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
 
