@@ -52,9 +52,15 @@ extern "C" {
 
 #define ARIDE_MAX_REPLAY (1 << 24) /* largest M: keeps the integer CDF below 2^63 */
 
+#define ARIDE_TRACE_RETRACE 0  /* Section 5.2: c_i = lambda * min(1, rho_i), product from i = t+1 */
+#define ARIDE_TRACE_VTRACE  1  /* the V-trace targets the paper contrasts Retrace with */
+
 typedef struct {
     float gamma;   /* discount */
     float lambda;  /* trace decay, in [0,1] */
+    int32_t mode;  /* ARIDE_TRACE_RETRACE (the paper's method) or ARIDE_TRACE_VTRACE */
+    float rho_bar; /* V-trace only: clip of the ratio that weights the TD error */
+    float c_bar;   /* V-trace only: clip of the ratio in the trace coefficient */
 } aride_retrace_cfg;
 
 typedef struct {
@@ -137,16 +143,34 @@ int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t ro
  * c_i = lambda min(1, rho_i).  Q == value when q is NULL (the paper's form).  The
  * corrected advantage of Section 5.1 is target - Q.
  *
+ * With cfg.mode = ARIDE_TRACE_VTRACE the same scan produces the V-trace targets (Section 2 and
+ * Appendix A.4.1 name them as the alternative A-RIDE is set against):
+ *     Delta_t = min(rho_bar, rho_t) delta_t + gamma * lambda * min(c_bar, rho_t) * Delta_{t+1}
+ * i.e. the step's own ratio weights its TD error and its own trace coefficient; td and rho are
+ * unchanged.
+ *
  *  logp_pi, logp_mu, reward, value  fp32 [N];  q fp32 [N] nullable;  boot fp32 [B]
  *  nullable (0);  traj_offsets int32 [B+1] non-decreasing;  target, td, rho fp32 [N]
  *  nullable.  Empty trajectories are allowed.
- * Errors: E_NULL, E_SHAPE (B<0, N<0), E_RANGE (N > 2^31-1).  B == 0 is a no-op.
+ * Errors: E_NULL, E_SHAPE (B<0, N<0), E_RANGE (N > 2^31-1, unknown mode).  B == 0 is a no-op.
  */
 int aride_retrace_targets(const float* logp_pi, const float* logp_mu, const float* reward,
                           const float* value, const float* q, const float* boot,
                           const int32_t* traj_offsets, int64_t B, int64_t N,
                           aride_retrace_cfg cfg, float* target, float* td, float* rho,
                           void* stream);
+
+/*
+ * mc_returns -- Section 5.1 (state-value function estimation): the Monte-Carlo return
+ *     ret[t] = sum_{k >= t, same trajectory} gamma^(k-t) reward[k]
+ * and the classification label the value network is trained on, label[t] = 1 if ret[t] > 0
+ * else 0.  Same reverse affine scan as retrace_targets (map X -> reward[t] + gamma X).
+ *
+ *  reward fp32 [N]; traj_offsets int32 [B+1]; ret, label fp32 [N], each nullable.
+ * Errors: E_NULL, E_SHAPE, E_RANGE.  B == 0 is a no-op.
+ */
+int aride_mc_returns(const float* reward, const int32_t* traj_offsets, int64_t B, int64_t N,
+                     float gamma, float* ret, float* label, void* stream);
 
 /*
  * compute_priorities -- Section 5.3 (DPER) with Appendix A.4.3's normalisation:

@@ -53,6 +53,11 @@ def _load():
     lib.oracle_sample_prioritized.restype = ctypes.c_int
     lib.oracle_sample_prioritized.argtypes = [_c_fp, ctypes.c_int64, _c_dp, ctypes.c_int64,
                                               _c_i64p, _c_dp]
+    lib.oracle_vtrace_targets.restype = ctypes.c_int
+    lib.oracle_vtrace_targets.argtypes = [_c_dp, _c_dp, _c_dp, _c_dp, _c_dp, _c_dp, _c_i32p, ctypes.c_int64,
+                                          ctypes.c_int64] + [ctypes.c_double] * 4 + [_c_dp, _c_dp, _c_dp]
+    lib.oracle_mc_returns.restype = ctypes.c_int
+    lib.oracle_mc_returns.argtypes = [_c_dp, _c_i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_double, _c_dp, _c_dp]
     lib.oracle_actor_loss_grad.restype = ctypes.c_int
     lib.oracle_actor_loss_grad.argtypes = [_c_u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _c_i32p,
                                            ctypes.c_int32, _c_dp, _c_dp, _c_dp, _c_dp, ctypes.c_double,
@@ -179,3 +184,34 @@ def actor_loss_grad(logits_bits, tokens, A, rho, target, baseline, beta, scale, 
     if rc != 0:
         raise ValueError(f"oracle_actor_loss_grad rc={rc}")
     return float(loss[0]), grad
+
+
+def vtrace_targets(logp_pi, logp_mu, reward, value, traj_offsets, gamma, lam, rho_bar, c_bar, q=None, boot=None):
+    """Returns dict(target[N], td[N], rho[N]) in fp64."""
+    lib = _load()
+    lp, lm, r, v = _f64(logp_pi), _f64(logp_mu), _f64(reward), _f64(value)
+    qq, bb = _f64(q), _f64(boot)
+    off = np.ascontiguousarray(np.asarray(traj_offsets, dtype=np.int32))
+    B, N = off.shape[0] - 1, lp.shape[0]
+    out = dict(target=np.zeros(N), td=np.zeros(N), rho=np.zeros(N))
+    rc = lib.oracle_vtrace_targets(_ptr(lp, _c_dp), _ptr(lm, _c_dp), _ptr(r, _c_dp), _ptr(v, _c_dp),
+                                   _ptr(qq, _c_dp), _ptr(bb, _c_dp), _ptr(off, _c_i32p), B, N, float(gamma),
+                                   float(lam), float(rho_bar), float(c_bar), _ptr(out["target"], _c_dp),
+                                   _ptr(out["td"], _c_dp), _ptr(out["rho"], _c_dp))
+    if rc != 0:
+        raise ValueError(f"oracle_vtrace_targets rc={rc}")
+    return out
+
+
+def mc_returns(reward, traj_offsets, gamma):
+    """Returns (ret[N], label[N]) in fp64."""
+    lib = _load()
+    r = _f64(reward)
+    off = np.ascontiguousarray(np.asarray(traj_offsets, dtype=np.int32))
+    N = r.shape[0]
+    ret, label = np.zeros(N), np.zeros(N)
+    rc = lib.oracle_mc_returns(_ptr(r, _c_dp), _ptr(off, _c_i32p), off.shape[0] - 1, N, float(gamma),
+                               _ptr(ret, _c_dp), _ptr(label, _c_dp))
+    if rc != 0:
+        raise ValueError(f"oracle_mc_returns rc={rc}")
+    return ret, label

@@ -302,3 +302,57 @@ int oracle_actor_loss_grad(const uint16_t* logits_bf16, int64_t R, int64_t V, in
     if (loss_out) *loss_out = scale * loss;
     return 0;
 }
+
+/*
+ * V-trace targets (Espeholt et al. 2018, the IMPALA paper), which the DistRL paper names as
+ * the standard alternative it sets Retrace against (Section 2; Appendix A.4.1):
+ *   v_s = V(x_s) + sum_{t=s}^{T-1} gamma^(t-s) (prod_{i=s}^{t-1} c_i) rho~_t delta_t,
+ *   rho~_t = min(rho_bar, rho_t),  c_i = lambda * min(c_bar, rho_i),
+ *   delta_t = r_t + gamma V(x_{t+1}) - Q_t   (Q == V when q is NULL).
+ * Peeling off the t = s term:  Delta_s = rho~_s delta_s + gamma c_s Delta_{s+1}; the step's OWN
+ * ratio enters both factors.  target = Q + Delta; td and rho as in oracle_retrace_targets.
+ */
+int oracle_vtrace_targets(const double* logp_pi, const double* logp_mu, const double* reward,
+                          const double* value, const double* q, const double* boot,
+                          const int32_t* traj_offsets, int64_t B, int64_t N, double gamma,
+                          double lambda, double rho_bar, double c_bar, double* target, double* td,
+                          double* rho) {
+    if (B < 0 || N < 0) return -2;
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t lo = traj_offsets[b], hi = traj_offsets[b + 1];
+        double Delta_next = 0.0;
+        for (int64_t t = hi - 1; t >= lo; --t) {
+            double v_next = (t == hi - 1) ? (boot ? boot[b] : 0.0) : value[t + 1];
+            double q_t = q ? q[t] : value[t];
+            double delta = reward[t] + gamma * v_next - q_t;
+            double rho_t = exp(logp_pi[t] - logp_mu[t]);
+            double rho_clip = rho_t < rho_bar ? rho_t : rho_bar;
+            double c_t = lambda * (rho_t < c_bar ? rho_t : c_bar);
+            double Delta = rho_clip * delta + ((t == hi - 1) ? 0.0 : gamma * c_t * Delta_next);
+            if (target) target[t] = q_t + Delta;
+            if (td) td[t] = delta;
+            if (rho) rho[t] = rho_t;
+            Delta_next = Delta;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Section 5.1, state-value function estimation: Monte-Carlo return G_t = sum_{k=t}^{T-1}
+ * gamma^(k-t) r_k within each trajectory, and the label 1[G_t > 0] of the value network's
+ * classification loss.
+ */
+int oracle_mc_returns(const double* reward, const int32_t* traj_offsets, int64_t B, int64_t N,
+                      double gamma, double* ret, double* label) {
+    if (B < 0 || N < 0) return -2;
+    for (int64_t b = 0; b < B; ++b) {
+        double G = 0.0;
+        for (int64_t t = traj_offsets[b + 1] - 1; t >= traj_offsets[b]; --t) {
+            G = reward[t] + gamma * G;
+            if (ret) ret[t] = G;
+            if (label) label[t] = G > 0.0 ? 1.0 : 0.0;
+        }
+    }
+    return 0;
+}

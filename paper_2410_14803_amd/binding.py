@@ -21,11 +21,15 @@ MAX_REPLAY = 1 << 24
 
 EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
            "aride_score_logits", "aride_retrace_targets", "aride_compute_priorities",
-           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad"]
+           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns"]
 
 
 class RetraceCfg(ctypes.Structure):
-    _fields_ = [("gamma", ctypes.c_float), ("lam", ctypes.c_float)]
+    _fields_ = [("gamma", ctypes.c_float), ("lam", ctypes.c_float), ("mode", ctypes.c_int32),
+                ("rho_bar", ctypes.c_float), ("c_bar", ctypes.c_float)]
+
+
+TRACE_RETRACE, TRACE_VTRACE = 0, 1
 
 
 class PrioCfg(ctypes.Structure):
@@ -75,6 +79,8 @@ def lib():
     L.aride_update_priorities.argtypes = [vp, i64, vp, vp, i64, f32, vp, sz, vp]
     L.aride_sample_prioritized.restype = ctypes.c_int
     L.aride_sample_prioritized.argtypes = [vp, i64, vp, sz, vp, i64, vp, vp, vp]
+    L.aride_mc_returns.restype = ctypes.c_int
+    L.aride_mc_returns.argtypes = [vp, vp, i64, i64, f32, vp, vp, vp]
     L.aride_actor_loss_grad.restype = ctypes.c_int
     L.aride_actor_loss_grad.argtypes = [vp, i64, i64, i64, vp, i32] + [vp] * 8 + [ActorCfg, vp, vp, vp]
     _lib = L
@@ -139,13 +145,14 @@ def score_logits(logits, tokens, A, ws, tok_logp=None, tok_ent=None, step_logp=N
 
 
 def retrace_targets(logp_pi, logp_mu, reward, value, traj_offsets, gamma, lam, q=None, boot=None,
-                    target=None, td=None, rho=None):
+                    target=None, td=None, rho=None, vtrace=False, rho_bar=1.0, c_bar=1.0):
     B = traj_offsets.numel() - 1
     N = logp_pi.numel()
     f = torch.float32
     rc = lib().aride_retrace_targets(_p(logp_pi, f), _p(logp_mu, f), _p(reward, f), _p(value, f), _p(q, f),
                                      _p(boot, f), _p(traj_offsets, torch.int32), B, N,
-                                     RetraceCfg(float(gamma), float(lam)), _p(target, f), _p(td, f),
+                                     RetraceCfg(float(gamma), float(lam), TRACE_VTRACE if vtrace else TRACE_RETRACE,
+                                                float(rho_bar), float(c_bar)), _p(target, f), _p(td, f),
                                      _p(rho, f), _stream())
     _check("aride_retrace_targets", rc)
 
@@ -194,3 +201,11 @@ def actor_loss_grad(logits, tokens, A, tok_logp, tok_ent, step_logp, step_ent, r
                                      _p(target, f), _p(baseline, f), _p(penalty, f), cfg, _p(grad),
                                      _p(loss, f), _stream())
     _check("aride_actor_loss_grad", rc)
+
+
+def mc_returns(reward, traj_offsets, gamma, ret=None, label=None):
+    B = traj_offsets.numel() - 1
+    f = torch.float32
+    rc = lib().aride_mc_returns(_p(reward, f), _p(traj_offsets, torch.int32), B, reward.numel(), float(gamma),
+                                _p(ret, f), _p(label, f), _stream())
+    _check("aride_mc_returns", rc)

@@ -7,8 +7,9 @@ namespace aride {
 hipError_t score_logits_launch(const uint16_t*, long long, int, long long, const int*, int, float*,
                                float*, float*, float*, uint32_t*, hipStream_t);
 hipError_t retrace_launch(const float*, const float*, const float*, const float*, const float*,
-                          const float*, const int*, int, int, float, float, float*, float*, float*,
-                          hipStream_t);
+                          const float*, const int*, int, int, float, float, int, float, float, float*, float*,
+                          float*, hipStream_t);
+hipError_t mc_returns_launch(const float*, const int*, int, int, float, float*, float*, hipStream_t);
 hipError_t priorities_launch(const float*, const float*, const float*, const int*, int, int, float,
                              float, float, float, float, float, int, float*, float*, hipStream_t);
 hipError_t update_launch(float*, long long, const long long*, const float*, int, float, WsHeader*,
@@ -92,8 +93,21 @@ int aride_retrace_targets(const float* logp_pi, const float* logp_mu, const floa
     if (B == 0) return ARIDE_OK;
     if (!traj_offsets) return ARIDE_E_NULL;
     if (N > 0 && (!logp_pi || !logp_mu || !reward || !value)) return ARIDE_E_NULL;
+    if (cfg.mode != ARIDE_TRACE_RETRACE && cfg.mode != ARIDE_TRACE_VTRACE) return ARIDE_E_RANGE;
     hipError_t err = retrace_launch(logp_pi, logp_mu, reward, value, q, boot, traj_offsets, (int)B,
-                                    (int)N, cfg.gamma, cfg.lambda, target, td, rho, (hipStream_t)stream);
+                                    (int)N, cfg.gamma, cfg.lambda, cfg.mode == ARIDE_TRACE_VTRACE, cfg.rho_bar,
+                                    cfg.c_bar, target, td, rho, (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_mc_returns(const float* reward, const int32_t* traj_offsets, int64_t B, int64_t N, float gamma,
+                     float* ret, float* label, void* stream) {
+    if (B < 0 || N < 0) return ARIDE_E_SHAPE;
+    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (B == 0) return ARIDE_OK;
+    if (!traj_offsets || (N > 0 && !reward)) return ARIDE_E_NULL;
+    hipError_t err = mc_returns_launch(reward, traj_offsets, (int)B, (int)N, gamma, ret, label,
+                                       (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
 

@@ -33,7 +33,7 @@ def test_error_codes_match_header():
     assert int(codes["ARIDE_E_ALIGN"]) == b.E_ALIGN and int(codes["ARIDE_E_RANGE"]) == b.E_RANGE
     assert int(codes["ARIDE_E_ZERO_MASS"]) == b.E_ZERO_MASS and int(codes["ARIDE_E_WORKSPACE"]) == b.E_WORKSPACE
     assert int(codes["ARIDE_E_HIP"]) == b.E_HIP
-    assert ctypes.sizeof(b.Status) == 24 and ctypes.sizeof(b.PrioCfg) == 28 and ctypes.sizeof(b.RetraceCfg) == 8
+    assert ctypes.sizeof(b.Status) == 24 and ctypes.sizeof(b.PrioCfg) == 28 and ctypes.sizeof(b.RetraceCfg) == 20
 
 
 def test_workspace_bytes(L):
@@ -71,7 +71,7 @@ def test_score_logits_rejects_bad_arguments(L):
 
 def test_retrace_and_priorities_reject_bad_arguments(L):
     a = P(4096)
-    cfg = b.RetraceCfg(0.9, 0.95)
+    cfg = b.RetraceCfg(0.9, 0.95, 0, 1.0, 1.0)
     f = L.aride_retrace_targets
     assert f(a, a, a, a, None, None, a, -1, 4, cfg, a, a, a, None) == b.E_SHAPE
     assert f(a, a, a, a, None, None, a, 2, -4, cfg, a, a, a, None) == b.E_SHAPE
@@ -79,6 +79,13 @@ def test_retrace_and_priorities_reject_bad_arguments(L):
     assert f(a, a, a, a, None, None, None, 2, 4, cfg, a, a, a, None) == b.E_NULL
     assert f(None, a, a, a, None, None, a, 2, 4, cfg, a, a, a, None) == b.E_NULL
     assert f(a, a, a, a, None, None, a, 0, 0, cfg, a, a, a, None) == b.OK
+    assert f(a, a, a, a, None, None, a, 2, 4, b.RetraceCfg(0.9, 0.95, 7, 1.0, 1.0), a, a, a, None) == b.E_RANGE
+    m = L.aride_mc_returns
+    assert m(a, a, -1, 4, 0.9, a, a, None) == b.E_SHAPE
+    assert m(a, None, 2, 4, 0.9, a, a, None) == b.E_NULL
+    assert m(None, a, 2, 4, 0.9, a, a, None) == b.E_NULL
+    assert m(a, a, 2, 1 << 31, 0.9, a, a, None) == b.E_RANGE
+    assert m(a, a, 0, 0, 0.9, a, a, None) == b.OK
     g = L.aride_compute_priorities
     pc = b.PrioCfg(1, 0.5, 0.1, 1, 1, 0, 1)
     assert g(a, a, a, a, -1, 4, pc, a, a, None) == b.E_SHAPE

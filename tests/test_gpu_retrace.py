@@ -134,3 +134,71 @@ def test_nullable_outputs_are_skipped():
     b.compute_priorities(x, x, x, off, (1, 1, 1))                   # both outputs NULL
     torch.cuda.synchronize()
     assert torch.all(tgt != 3.0)
+
+
+@pytest.mark.parametrize("rho_bar,c_bar,lam", [(1.0, 1.0, 1.0), (2.0, 0.7, 0.9)])
+def test_vtrace_mode(oracle, rho_bar, c_bar, lam):
+    cfg = synth.CONFIGS[3]
+    lens = [1, 2, 63, 64, 65, 255, 256, 257, 700, 0, 3]
+    off_np, off, lp, lm, si, boot = make_case(lens, 900, cfg)
+    N = lp.numel()
+    out = {k: torch.full((N,), 7.0, device=DEV) for k in ("target", "td", "rho")}
+    b.retrace_targets(lp, lm, si["reward"], si["value"], off, 0.97, lam, q=si["q"], boot=boot, vtrace=True,
+                      rho_bar=rho_bar, c_bar=c_bar, **out)
+    torch.cuda.synchronize()
+    want = oracle.vtrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, 0.97, lam, rho_bar,
+                                 c_bar, q=npf(si["q"]), boot=npf(boot))
+    for k in ("target", "td", "rho"):
+        assert_close(npf(out[k]), want[k], 1.0, f"vtrace {k}")
+
+
+def test_vtrace_config3_full(oracle):
+    cfg = synth.CONFIGS[3]
+    seed = synth.BASE_SEED + cfg.index
+    off_np = synth.trajectory_offsets(cfg, seed)
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=DEV)
+    lp = synth.policy_logprobs(N, seed + 3, DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 4, DEV)
+    lm = lp + si["mu_noise"]
+    tgt = torch.empty(N, device=DEV)
+    b.retrace_targets(lp, lm, si["reward"], si["value"], off, cfg.gamma, 1.0, target=tgt, vtrace=True)
+    torch.cuda.synchronize()
+    want = oracle.vtrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, cfg.gamma, 1.0, 1.0, 1.0)
+    assert_close(npf(tgt), want["target"], 1.0, "vtrace config3")
+
+
+@pytest.mark.parametrize("ci", [0, 1, 3])
+def test_mc_returns(oracle, ci):
+    cfg = synth.CONFIGS[ci]
+    seed = synth.BASE_SEED + cfg.index
+    off_np = synth.trajectory_offsets(cfg, seed)
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 4, DEV)
+    ret = torch.full((N,), 7.0, device=DEV)
+    label = torch.full((N,), 7.0, device=DEV)
+    b.mc_returns(si["reward"], off, cfg.gamma, ret=ret, label=label)
+    torch.cuda.synchronize()
+    o_ret, o_label = oracle.mc_returns(npf(si["reward"]), off_np, cfg.gamma)
+    assert_close(npf(ret), o_ret, 1.0, f"config{ci} mc return")
+    # the label is decided by the sign of a sum of non-negative rewards: no rounding can flip it
+    np.testing.assert_array_equal(npf(label), o_label)
+
+
+def test_mc_returns_ragged_and_signed(oracle):
+    lens = [0, 1, 64, 65, 256, 257, 1000, 2]
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    off = torch.as_tensor(off_np, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(1)
+    r = torch.randn(int(off_np[-1]), generator=g, device=DEV) * (torch.rand(int(off_np[-1]), generator=g, device=DEV) < 0.3)
+    ret = torch.empty_like(r); label = torch.empty_like(r)
+    b.mc_returns(r, off, 0.99, ret=ret, label=label)
+    b.mc_returns(r, off, 0.99, ret=None, label=None)          # both outputs skipped
+    torch.cuda.synchronize()
+    o_ret, o_label = oracle.mc_returns(npf(r), off_np, 0.99)
+    assert_close(npf(ret), o_ret, 1.0, "signed mc return")
+    # labels agree wherever the return is not within rounding distance of zero, and always match the device's own sign
+    clear = np.abs(o_ret) > 1e-4
+    np.testing.assert_array_equal(npf(label)[clear], o_label[clear])
+    np.testing.assert_array_equal(npf(label), (npf(ret) > 0).astype(np.float32))
