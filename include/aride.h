@@ -208,6 +208,23 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
                             int64_t K, float alpha, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * replay_insert -- Appendix A.4.2 (circular replay buffer of fixed capacity M): append K new
+ * entries; entry k is written at slot (cursor + k) mod M, overwriting the oldest entries, and
+ * the buffer index advances as i <- (i + 1) mod M per entry.  The stored value is the entry's
+ * sampling weight pow(max(prio[k], 0), alpha); the entry's payload belongs in the caller's own
+ * arrays at the same slot, reported through slots_out.  When K > M only the last M entries
+ * survive and the earlier ones report slot -1.  The sampling index is rebuilt afterwards (as
+ * by aride_update_priorities with K = 0).
+ *
+ *  weights fp32 [M] in/out (16-byte aligned); cursor in [0, M); prio fp32 [K];
+ *  slots_out int64 [K] nullable; cursor_out host pointer, nullable: receives (cursor + K) mod M.
+ * Errors: E_NULL, E_SHAPE, E_ALIGN, E_RANGE (cursor outside [0,M), alpha < 0), E_WORKSPACE.
+ */
+int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* prio, int64_t K,
+                        float alpha, int64_t* slots_out, void* ws, size_t ws_bytes,
+                        int64_t* cursor_out /* host */, void* stream);
+
+/*
  * sample_prioritized -- Appendix A.4.2: draw index i with probability
  * P(i) = w_i / sum_j w_j  (w = p^alpha), realised on exact integers so the result is a
  * function of the stored weight bits and the uniform alone:

@@ -58,6 +58,9 @@ def _load():
                                           ctypes.c_int64] + [ctypes.c_double] * 4 + [_c_dp, _c_dp, _c_dp]
     lib.oracle_mc_returns.restype = ctypes.c_int
     lib.oracle_mc_returns.argtypes = [_c_dp, _c_i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_double, _c_dp, _c_dp]
+    lib.oracle_replay_insert.restype = ctypes.c_int64
+    lib.oracle_replay_insert.argtypes = [_c_fp, ctypes.c_int64, ctypes.c_int64, _c_fp, ctypes.c_int64,
+                                         ctypes.c_float, _c_i64p]
     lib.oracle_actor_loss_grad.restype = ctypes.c_int
     lib.oracle_actor_loss_grad.argtypes = [_c_u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _c_i32p,
                                            ctypes.c_int32, _c_dp, _c_dp, _c_dp, _c_dp, ctypes.c_double,
@@ -215,3 +218,14 @@ def mc_returns(reward, traj_offsets, gamma):
     if rc != 0:
         raise ValueError(f"oracle_mc_returns rc={rc}")
     return ret, label
+
+
+def replay_insert(weights, cursor, prio, alpha):
+    """In place on a float32 numpy array; returns (new_cursor, slots[K] int64)."""
+    lib = _load()
+    assert weights.dtype == np.float32 and weights.flags["C_CONTIGUOUS"]
+    pp = np.ascontiguousarray(np.asarray(prio, dtype=np.float32))
+    slots = np.zeros(pp.shape[0], dtype=np.int64)
+    cur = lib.oracle_replay_insert(_ptr(weights, _c_fp), weights.shape[0], int(cursor), _ptr(pp, _c_fp),
+                                   pp.shape[0], np.float32(alpha), _ptr(slots, _c_i64p))
+    return int(cur), slots

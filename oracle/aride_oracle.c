@@ -356,3 +356,26 @@ int oracle_mc_returns(const double* reward, const int32_t* traj_offsets, int64_t
     }
     return 0;
 }
+
+/*
+ * Appendix A.4.2, circular replay buffer of fixed capacity M: each new entry is written at the
+ * buffer index i, which then advances as i <- (i + 1) mod M, so that new experiences overwrite
+ * the oldest ones.  Here the stored value is the entry's sampling weight prio^alpha (the payload
+ * lives in the caller's arrays at the same slot).  slots_out[k] receives the slot entry k was
+ * written to, or -1 if a later entry of the same batch overwrote it (only possible when K > M).
+ * Returns the advanced index.
+ */
+int64_t oracle_replay_insert(float* weights, int64_t M, int64_t cursor, const float* prio, int64_t K,
+                             float alpha, int64_t* slots_out) {
+    int64_t i = cursor;
+    for (int64_t k = 0; k < K; ++k) {
+        double p = (double)prio[k];
+        if (!(p > 0.0)) p = 0.0;
+        weights[i] = (float)pow(p, (double)alpha);
+        if (slots_out) slots_out[k] = i;
+        i = (i + 1) % M;
+    }
+    if (slots_out)
+        for (int64_t k = 0; k + M < K; ++k) slots_out[k] = -1; /* overwritten by entry k + M */
+    return i;
+}

@@ -21,7 +21,7 @@ MAX_REPLAY = 1 << 24
 
 EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
            "aride_score_logits", "aride_retrace_targets", "aride_compute_priorities",
-           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns"]
+           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns", "aride_replay_insert"]
 
 
 class RetraceCfg(ctypes.Structure):
@@ -79,6 +79,8 @@ def lib():
     L.aride_update_priorities.argtypes = [vp, i64, vp, vp, i64, f32, vp, sz, vp]
     L.aride_sample_prioritized.restype = ctypes.c_int
     L.aride_sample_prioritized.argtypes = [vp, i64, vp, sz, vp, i64, vp, vp, vp]
+    L.aride_replay_insert.restype = ctypes.c_int
+    L.aride_replay_insert.argtypes = [vp, i64, i64, vp, i64, f32, vp, vp, sz, ctypes.POINTER(ctypes.c_int64), vp]
     L.aride_mc_returns.restype = ctypes.c_int
     L.aride_mc_returns.argtypes = [vp, vp, i64, i64, f32, vp, vp, vp]
     L.aride_actor_loss_grad.restype = ctypes.c_int
@@ -209,3 +211,14 @@ def mc_returns(reward, traj_offsets, gamma, ret=None, label=None):
     rc = lib().aride_mc_returns(_p(reward, f), _p(traj_offsets, torch.int32), B, reward.numel(), float(gamma),
                                 _p(ret, f), _p(label, f), _stream())
     _check("aride_mc_returns", rc)
+
+
+def replay_insert(weights, cursor, prio, alpha, ws, slots_out=None):
+    """Appends prio.numel() entries at the circular cursor; returns the advanced cursor."""
+    new_cursor = ctypes.c_int64(-1)
+    rc = lib().aride_replay_insert(_p(weights, torch.float32), weights.numel(), int(cursor),
+                                   _p(prio, torch.float32), prio.numel(), float(alpha),
+                                   _p(slots_out, torch.int64), ws.ptr, ws.nbytes, ctypes.byref(new_cursor),
+                                   _stream())
+    _check("aride_replay_insert", rc)
+    return new_cursor.value

@@ -14,6 +14,8 @@ hipError_t priorities_launch(const float*, const float*, const float*, const int
                              float, float, float, float, float, int, float*, float*, hipStream_t);
 hipError_t update_launch(float*, long long, const long long*, const float*, int, float, WsHeader*,
                          unsigned long long*, unsigned long long*, uint32_t*, hipStream_t);
+hipError_t insert_launch(float*, long long, long long, const float*, long long, float, long long*, WsHeader*,
+                         unsigned long long*, unsigned long long*, uint32_t*, hipStream_t);
 hipError_t sample_launch(const float*, long long, const WsHeader*, const unsigned long long*,
                          const unsigned long long*, const double*, int, long long*, float*, uint32_t*,
                          hipStream_t);
@@ -150,6 +152,25 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
     hipError_t err = update_launch(weights, M, (const long long*)idx, prio, (int)K, alpha, hdr, block_cum,
                                    super_cum, partial_max, (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* prio, int64_t K, float alpha,
+                        int64_t* slots_out, void* ws, size_t ws_bytes, int64_t* cursor_out, void* stream) {
+    if (K < 0) return ARIDE_E_SHAPE;
+    int rc = check_replay(weights, M, ws, ws_bytes);
+    if (rc != ARIDE_OK) return rc;
+    if (cursor < 0 || cursor >= M || !(alpha >= 0.f) || K > ((int64_t)1 << 40)) return ARIDE_E_RANGE;
+    if (K > 0 && !prio) return ARIDE_E_NULL;
+    if (slots_out && misaligned(slots_out, 8)) return ARIDE_E_ALIGN;
+    WsHeader* hdr = (WsHeader*)ws;
+    unsigned long long* super_cum = (unsigned long long*)((char*)ws + kHeaderBytes);
+    uint32_t* partial_max = (uint32_t*)((char*)ws + kHeaderBytes + kSuperBytes);
+    unsigned long long* block_cum = (unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
+    hipError_t err = insert_launch(weights, M, cursor, prio, K, alpha, (long long*)slots_out, hdr, block_cum,
+                                   super_cum, partial_max, (hipStream_t)stream);
+    if (err != hipSuccess) return ARIDE_E_HIP;
+    if (cursor_out) *cursor_out = (cursor + K % M) % M;
+    return ARIDE_OK;
 }
 
 int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t ws_bytes,

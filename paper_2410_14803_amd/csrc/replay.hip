@@ -69,6 +69,22 @@ __global__ __launch_bounds__(256) void k_update_commit(
     weights[i] = (float)pow(p, (double)alpha);
 }
 
+// Appendix A.4.2, circular buffer: entry k of the batch goes to slot (cursor + k) mod M.  When
+// the batch is longer than the buffer only its last M entries survive (what inserting one at a
+// time would leave); the others report slot -1.  Surviving slots are distinct, so no tag pass.
+__global__ __launch_bounds__(256) void k_insert(float* __restrict__ weights, long long M, long long cursor,
+                                                const float* __restrict__ prio, long long K, float alpha,
+                                                long long* __restrict__ slots_out) {
+    const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    if (k + M < K) { if (slots_out) slots_out[k] = -1; return; }
+    const long long slot = (cursor + k) % M;
+    double p = (double)prio[k];
+    if (!(p > 0.0)) p = 0.0;
+    weights[slot] = (float)pow(p, (double)alpha);
+    if (slots_out) slots_out[k] = slot;
+}
+
 // Pass A of the rebuild: largest valid weight (order-free, exact).  Each of the kMaxParts
 // workgroups writes the maximum of its share to partial_max; the consumers reduce those 1024
 // words themselves.  (One atomic per wave onto a single header word was measured at ~160 us
@@ -441,6 +457,15 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     }
     hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, super_cum, nsuper, partial_max, hdr);
     return hipGetLastError();
+}
+
+hipError_t insert_launch(float* weights, long long M, long long cursor, const float* prio, long long K,
+                         float alpha, long long* slots_out, WsHeader* hdr, unsigned long long* block_cum,
+                         unsigned long long* super_cum, uint32_t* partial_max, hipStream_t st) {
+    if (K > 0)
+        hipLaunchKernelGGL(k_insert, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, weights, M, cursor, prio,
+                           K, alpha, slots_out);
+    return update_launch(weights, M, nullptr, nullptr, 0, alpha, hdr, block_cum, super_cum, partial_max, st);
 }
 
 hipError_t sample_launch(const float* weights, long long M, const WsHeader* hdr,

@@ -120,6 +120,13 @@ def test_replay_rejects_bad_arguments(L):
     assert s(w, 1000, ws, need, a, 4, None, None, None) == b.E_NULL
     assert s(w, 1000, ws, need, P(16388), 4, a, None, None) == b.E_ALIGN
     assert s(w, 1000, ws, need, a, 0, a, None, None) == b.OK
+    ins = L.aride_replay_insert
+    assert ins(w, 1000, 0, a, -1, 0.6, None, ws, need, None, None) == b.E_SHAPE
+    assert ins(w, 1000, 1000, a, 4, 0.6, None, ws, need, None, None) == b.E_RANGE     # cursor outside the buffer
+    assert ins(w, 1000, -1, a, 4, 0.6, None, ws, need, None, None) == b.E_RANGE
+    assert ins(w, 1000, 0, None, 4, 0.6, None, ws, need, None, None) == b.E_NULL
+    assert ins(w, 1000, 0, a, 4, 0.6, None, ws, need - 1, None, None) == b.E_WORKSPACE
+    assert ins(w, 1000, 0, a, 4, 0.6, P(16388), ws, need, None, None) == b.E_ALIGN
     assert L.aride_workspace_init(None, 256, None) == b.E_WORKSPACE
     assert L.aride_workspace_init(ws, 100, None) == b.E_WORKSPACE
     assert L.aride_status_read(None, None, None) == b.E_NULL

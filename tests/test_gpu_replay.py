@@ -192,3 +192,43 @@ def test_config4_replay_at_scale_chain(oracle):
     st, rc = ws.status()
     q, total = oracle.quantise_weights(npf(w))
     assert rc == b.OK and st.total == total
+
+
+@pytest.mark.parametrize("M,K,cursor", [(5, 3, 0), (5, 4, 3), (17, 60, 11), (1000, 0, 7), (4096, 256, 4000),
+                                        (65536, 1024, 65000), (70001, 200000, 123)])
+def test_circular_insert(oracle, M, K, cursor):
+    print(f"case M={M} K={K}", flush=True)
+    w = fresh(M, "exp", 600 + M, 0.6, oracle)
+    wo = npf(w).copy()
+    ws = b.Workspace(M)
+    prio = synth.replay_priorities(max(K, 1), "lognormal", 601 + K, DEV)[:K].contiguous()
+    slots = torch.full((K,), -7, dtype=torch.int64, device=DEV)
+    new_cursor = b.replay_insert(w, cursor, prio, 0.6, ws, slots_out=slots)
+    torch.cuda.synchronize()
+    o_cursor, o_slots = oracle.replay_insert(wo, cursor, npf(prio), 0.6)
+    assert new_cursor == o_cursor == (cursor + K) % M
+    np.testing.assert_array_equal(npf(slots), o_slots)
+    np.testing.assert_allclose(npf(w), wo, rtol=1e-6)
+    check_sample(oracle, w, synth.uniforms(1500, 602 + M, DEV), ws, f"after insert M={M}")
+
+
+def test_insert_then_sample_then_update_cycle(oracle):
+    # a small replay life cycle: trajectories arrive, a batch is drawn, its priorities are refreshed
+    M = 3000
+    ws = b.Workspace(M)
+    w = torch.zeros(M, device=DEV)
+    wo = np.zeros(M, np.float32)
+    cursor = 0
+    for it in range(8):
+        K = 700
+        prio = synth.replay_priorities(K, "exp", 700 + it, DEV)
+        new_cursor = b.replay_insert(w, cursor, prio, 0.6, ws)
+        o_cursor, _ = oracle.replay_insert(wo, cursor, npf(prio), 0.6)
+        assert new_cursor == o_cursor
+        cursor = new_cursor
+        idx = check_sample(oracle, w, synth.uniforms(300, 800 + it, DEV), ws, f"cycle {it}")
+        newp = synth.replay_priorities(300, "lognormal", 900 + it, DEV)
+        b.update_priorities(w, torch.as_tensor(idx, device=DEV), newp, 0.6, ws)
+        torch.cuda.synchronize()
+        wo = npf(w).copy()          # continue from the device's weight bits
+    assert cursor == (8 * 700) % M

@@ -222,3 +222,39 @@ def test_chi_square_sanity(oracle):
     expected = q.astype(np.float64) / total * n
     chi2 = np.sum((np.bincount(idx, minlength=40) - expected) ** 2 / expected)
     assert chi2 < 39 + 6 * math.sqrt(2 * 39)     # mean dof, +6 sigma
+
+
+# ---------------------------------------------------------------- circular insert (Appendix A.4.2)
+
+def test_circular_insert_wraps_and_overwrites_oldest(oracle):
+    M = 5
+    w = np.zeros(M, np.float32)
+    cur, slots = oracle.replay_insert(w, 0, [1.0, 4.0, 9.0], 0.5)
+    assert cur == 3 and list(slots) == [0, 1, 2]
+    np.testing.assert_array_equal(w, [1, 2, 3, 0, 0])
+    cur, slots = oracle.replay_insert(w, cur, [16.0, 25.0, 36.0, 49.0], 0.5)     # wraps past the end
+    assert cur == 2 and list(slots) == [3, 4, 0, 1]
+    np.testing.assert_array_equal(w, [6, 7, 3, 4, 5])                            # the two oldest were overwritten
+
+
+def test_circular_insert_batch_equals_one_by_one(oracle):
+    rng = np.random.default_rng(30)
+    M = 17
+    p = rng.random(60).astype(np.float32) * 4
+    wa = np.zeros(M, np.float32); wb = np.zeros(M, np.float32)
+    cur_a, slots = oracle.replay_insert(wa, 11, p, 0.6)
+    cur_b = 11
+    for x in p:                                  # the paper's rule, i <- (i + 1) mod N, one entry at a time
+        wb[cur_b] = np.float32(float(x) ** np.float64(np.float32(0.6)))
+        cur_b = (cur_b + 1) % M
+    assert cur_a == cur_b == (11 + 60) % M
+    np.testing.assert_allclose(wa, wb, rtol=1e-7)
+    # more entries than capacity: only the last M survive, the earlier ones report slot -1
+    assert np.all(slots[:60 - M] == -1) and sorted(slots[60 - M:]) == list(range(M))
+    np.testing.assert_array_equal(slots[60 - M:], (11 + np.arange(60 - M, 60)) % M)
+
+
+def test_circular_insert_empty_batch(oracle):
+    w = np.ones(4, np.float32)
+    cur, slots = oracle.replay_insert(w, 3, [], 0.6)
+    assert cur == 3 and len(slots) == 0 and np.all(w == 1)
