@@ -29,6 +29,9 @@ namespace aride {
 #ifndef ARIDE_SCORE_PIPELINE
 #define ARIDE_SCORE_PIPELINE 0  // 1: issue the next batch of loads before reducing the current one
 #endif
+#ifndef ARIDE_SCORE_WAVES
+#define ARIDE_SCORE_WAVES 4     // waves per workgroup (a multiple of ARIDE_SCORE_WPR)
+#endif
 #ifndef ARIDE_SCORE_NT
 #define ARIDE_SCORE_NT 1        // 1: non-temporal loads
 #endif
@@ -130,13 +133,13 @@ __device__ __forceinline__ void to_common(float negk, float s, float t, float kc
 }
 
 template <int WPR, int UNROLL>
-__global__ __launch_bounds__(256) void k_score_rows(
+__global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
     const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
-    constexpr int kRowsPerBlock = 4 / WPR;
+    constexpr int kRowsPerBlock = ARIDE_SCORE_WAVES / WPR;
     constexpr int kTPR = kWave * WPR;  // threads per row
-    __shared__ float sh[WPR > 1 ? 4 * 3 : 1];
+    __shared__ float sh[WPR > 1 ? ARIDE_SCORE_WAVES * 3 : 1];
 
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
@@ -274,9 +277,9 @@ template <int WPR, int UNROLL>
 static hipError_t launch_rows(const uint16_t* logits, long long R, int V, long long stride,
                               const int* tokens, float* tl, float* te, uint32_t* status,
                               hipStream_t st) {
-    constexpr int rpb = 4 / WPR;
+    constexpr int rpb = ARIDE_SCORE_WAVES / WPR;
     long long blocks = (R + rpb - 1) / rpb;
-    hipLaunchKernelGGL((k_score_rows<WPR, UNROLL>), dim3((unsigned)blocks), dim3(256), 0, st,
+    hipLaunchKernelGGL((k_score_rows<WPR, UNROLL>), dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES), 0, st,
                        logits, R, V, stride, tokens, tl, te, status);
     return hipGetLastError();
 }
