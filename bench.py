@@ -148,11 +148,14 @@ def main():
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+    # HIP events bracket the logit sweep on every 4th step only: an event costs a barrier packet
+    # on the stream, and bracketing every step would slow the very loop being timed by ~3 %
+    every = 4
+    events = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for i in range(0, args.steps, every)}
     t0 = time.perf_counter()
     for i in range(args.steps):
-        one_step(args.warmup + i, events[i])
+        one_step(args.warmup + i, events.get(i))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
@@ -176,7 +179,7 @@ def main():
     value = N * args.steps / elapsed
     # dominant kernel: the logit sweep.  Algorithmic bytes per launch: every bf16 logit once,
     # one int32 token per row, two fp32 results per row.
-    sweep_ms = sum(a.elapsed_time(c) for a, c in events) / args.steps
+    sweep_ms = sum(a.elapsed_time(c) for a, c in events.values()) / len(events)
     import hashlib
     src = os.path.join(ROOT, "paper_2410_14803_amd", "csrc", "score_logits.hip")
     same_kernel = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == TRAFFIC["source_sha256"]
