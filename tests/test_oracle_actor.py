@@ -47,7 +47,7 @@ def test_against_autograd(oracle, seed, beta):
     xd = torch.from_numpy(synth.bf16_bits_to_f64(bits)).requires_grad_(True)
     L = _torch_loss(xd, tok, A, rho, target, base, pen, beta, lam, scale)
     L.backward()
-    assert loss == pytest.approx(float(L), rel=1e-12, abs=1e-13)
+    assert loss == pytest.approx(float(L.detach()), rel=1e-12, abs=1e-13)
     np.testing.assert_allclose(grad, xd.grad.numpy(), rtol=1e-10, atol=1e-13)
     assert np.all(grad[1] == 0)            # the padding row has no gradient
 
