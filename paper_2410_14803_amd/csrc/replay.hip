@@ -69,6 +69,29 @@ __global__ __launch_bounds__(256) void k_update_commit(
     weights[i] = (float)pow(p, (double)alpha);
 }
 
+// Both passes in one workgroup for batches of up to kSmallBatch entries: a workgroup barrier
+// separates them, the tags are written and read with device-scope atomics.
+__global__ __launch_bounds__(1024) void k_update_scatter_small(
+    float* __restrict__ weights, long long M, const long long* __restrict__ idx, const float* __restrict__ prio,
+    int K, float alpha, WsHeader* hdr) {
+    uint32_t* wbits = reinterpret_cast<uint32_t*>(weights);
+    for (int k = threadIdx.x; k < K; k += 1024) {
+        const long long i = idx[k];
+        if (i < 0 || i >= M) { atomicOr(&hdr->flags, 0x8u); continue; }
+        atomicMax(wbits + i, kTagBase | (uint32_t)k);
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < K; k += 1024) {
+        const long long i = idx[k];
+        if (i < 0 || i >= M) continue;
+        const uint32_t seen = __hip_atomic_load(wbits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen != (kTagBase | (uint32_t)k)) continue;
+        double p = (double)prio[k];
+        if (!(p > 0.0)) p = 0.0;
+        __hip_atomic_store(weights + i, (float)pow(p, (double)alpha), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // Appendix A.4.2, circular buffer: entry k of the batch goes to slot (cursor + k) mod M.  When
 // the batch is longer than the buffer only its last M entries survive (what inserting one at a
 // time would leave); the others report slot -1.  Surviving slots are distinct, so no tag pass.
@@ -223,14 +246,28 @@ __global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ we
 }
 
 // ... followed by the in-place inclusive scan of each super-block's 256 raw block sums.
+// With a single super-block (gridDim.x == 1) it also does the work of k_prefix_super.
 __global__ __launch_bounds__(256) void k_scan_supers(unsigned long long* __restrict__ block_cum, int nblk,
-                                                     unsigned long long* __restrict__ super_raw) {
+                                                     unsigned long long* __restrict__ super_raw,
+                                                     const uint32_t* __restrict__ partial_max, WsHeader* hdr) {
     __shared__ unsigned long long wave_tot4[4];
+    __shared__ uint32_t wave_best[4];
     const int blk = blockIdx.x * kSuperBlocks + threadIdx.x;
     unsigned long long total = 0ull;
     const unsigned long long incl = scan256(blk < nblk ? block_cum[blk] : 0ull, wave_tot4, total);
     if (blk < nblk) block_cum[blk] = incl;
-    if (threadIdx.x == 0) super_raw[blockIdx.x] = total;
+    if (gridDim.x > 1) {
+        if (threadIdx.x == 0) super_raw[blockIdx.x] = total;
+        return;
+    }
+    const uint32_t wb = reduce_partial_max<256>(partial_max, wave_best);
+    super_raw[threadIdx.x] = total;            // all 256 entries: the only super-block, then padding
+    if (threadIdx.x == 0) {
+        hdr->wmax_bits = wb;
+        hdr->total = total;
+        hdr->exponent = wb ? exponent_of(wb) : 0;
+        if (total == 0ull) atomicOr(&hdr->flags, 0x4u);
+    }
 }
 
 // Pass C: inclusive prefix of the (at most 256) super-block totals, padded with Total; also
@@ -441,7 +478,9 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
                            hdr, block_cum, nblk, super_cum);
         return hipGetLastError();
     }
-    if (K > 0) {
+    if (K > 0 && K <= kSmallBatch) {
+        hipLaunchKernelGGL(k_update_scatter_small, dim3(1), dim3(1024), 0, st, weights, M, idx, prio, K, alpha, hdr);
+    } else if (K > 0) {
         const unsigned g = (unsigned)((K + 255) / 256);
         hipLaunchKernelGGL(k_update_tag, dim3(g), dim3(256), 0, st, weights, M, idx, K, hdr);
         hipLaunchKernelGGL(k_update_commit, dim3(g), dim3(256), 0, st, weights, M, idx, prio, K, alpha);
@@ -453,7 +492,9 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     } else {
         hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M,
                            partial_max, block_cum, nblk);
-        hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, block_cum, nblk, super_cum);
+        hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, block_cum, nblk, super_cum,
+                           partial_max, hdr);
+        if (nsuper == 1) return hipGetLastError();   // the scan kernel finalised the index itself
     }
     hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, super_cum, nsuper, partial_max, hdr);
     return hipGetLastError();
