@@ -22,19 +22,17 @@ namespace aride {
 
 constexpr uint32_t kTagBase = 0xFF800000u;
 
-// q = floor(w * 2^(39-e)) computed on the bit pattern; negative, NaN and infinite
-// weights (and -0) carry no mass.
+// q = floor(w * 2^(39-e)); negative, NaN and infinite weights (and -0) carry no mass.
+// Exact in fp32: scaling by a power of two (v_ldexp_f32) does not touch the 24-bit mantissa,
+// x < 2^39 splits into hi = floor(x / 2^32) and lo = x - hi * 2^32, both exact, and
+// v_cvt_u32_f32 truncates.  A result below the normal range floors to 0 either way.
 __device__ __forceinline__ unsigned long long quantise(float w, int e) {
     const uint32_t b = float_to_bits(w);
-    if (b >= 0x7F800000u) return 0ull;
-    uint32_t E = b >> 23;
-    uint32_t mant = b & 0x7FFFFFu;
-    if (E == 0) E = 1; else mant |= 0x800000u;   // subnormal: no implicit bit, exponent of 1
-    // w = mant * 2^(E-150)  =>  q = floor(mant * 2^(E - 111 - e))
-    int sh = (int)E - 111 - e;
-    if (sh >= 0) return (unsigned long long)mant << (sh > 39 ? 39 : sh);
-    sh = -sh;
-    return sh >= 24 ? 0ull : (unsigned long long)(mant >> sh);
+    const float wc = b < 0x7F800000u ? w : 0.f;
+    const float x = ldexpf(wc, 39 - e);
+    const uint32_t hi = (uint32_t)(x * 2.3283064365386963e-10f);             // 2^-32
+    const uint32_t lo = (uint32_t)fmaf(-(float)hi, 4294967296.f, x);
+    return ((unsigned long long)hi << 32) | lo;
 }
 
 // e = ilogb(wmax) + 1 from the bit pattern of a positive finite float.
