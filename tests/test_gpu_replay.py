@@ -158,9 +158,10 @@ def test_config_sample_then_update(oracle, ci):
 
 
 def test_config4_replay_at_scale_chain(oracle):
-    # sample -> recompute priorities from synthetic TD errors -> scatter -> rebuild, repeatedly.
-    # Every iteration the oracle samples from the weight bits the device holds, and the free-running
-    # oracle copy of the buffer tracks how far pow() in the last place lets the two drift.
+    # 100 iterations of sample -> recompute priorities from synthetic TD errors -> scatter -> rebuild.
+    # On the first five and every tenth iteration the oracle draws from the weight bits the device
+    # holds (bit-exact indices); a free-running oracle copy of the buffer, updated with the host's
+    # pow(), shows how far the last place of pow() lets the two drift.
     cfg = synth.CONFIGS[4]
     seed = synth.BASE_SEED + cfg.index
     M, K = cfg.M, cfg.K
@@ -175,20 +176,27 @@ def test_config4_replay_at_scale_chain(oracle):
     free = np.zeros(M, np.float32)
     oracle.update_priorities(free, np.arange(M), npf(p0), cfg.alpha)
     np.testing.assert_allclose(npf(w), free, rtol=1e-6)
-    iters = 12
+    iters = 100
     drift = 0
     for it in range(iters):
         u = synth.uniforms(K, seed + 100 + it, DEV)
         idx, _ = gpu_sample(w, u, ws, want_prob=False)
-        oi, _, rc = oracle.sample_prioritized(npf(w), npf(u))
-        np.testing.assert_array_equal(idx, oi, err_msg=f"iteration {it}")
-        fi, _, _ = oracle.sample_prioritized(free, npf(u))
-        drift += int((fi != idx).sum())
         td = synth.td_errors(K, seed + 200 + it, DEV)
         prio = td.abs()                                   # w = (1, 0, 0): priority = |delta|
+        if it < 5 or it % 10 == 9:
+            # the oracle draws from the weight bits the device holds ...
+            oi, _, rc = oracle.sample_prioritized(npf(w), npf(u))
+            np.testing.assert_array_equal(idx, oi, err_msg=f"iteration {it}")
+            # ... and, free-running from its own copy of the buffer, shows how far pow() lets the two drift
+            fi, _, _ = oracle.sample_prioritized(free, npf(u))
+            drift += int((fi != idx).sum())
+            print(f"iter {it} ok, free-running index mismatches so far {drift}", flush=True)
+        else:
+            assert idx.min() >= 0 and idx.max() < M
         b.update_priorities(w, torch.as_tensor(idx, device=DEV), prio, cfg.alpha, ws)
-        oracle.update_priorities(free, fi, npf(prio), cfg.alpha)
-        print(f"iter {it} ok, free-running index mismatches so far {drift}", flush=True)
+        oracle.update_priorities(free, idx, npf(prio), cfg.alpha)    # same indices, host pow
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(npf(w), free, rtol=1e-6)              # a hundred updates later
     st, rc = ws.status()
     q, total = oracle.quantise_weights(npf(w))
     assert rc == b.OK and st.total == total
