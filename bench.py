@@ -72,6 +72,92 @@ def bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, ste
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
 
 
+def _timed(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, e0.elapsed_time(e1) / steps
+
+
+def bench_retrace(args, b, torch, synth, dev):
+    """One step = retrace_targets + compute_priorities over the long-scan batch (config 3)."""
+    cfg = synth.CONFIGS[3]
+    seed = synth.BASE_SEED + cfg.index
+    off_np = synth.trajectory_offsets(cfg, seed)
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=dev)
+    lp = synth.policy_logprobs(N, seed + 3, dev)
+    si = synth.step_inputs(cfg, off_np, seed + 4, dev)
+    lm = lp + si["mu_noise"]
+    ent = torch.rand(N, device=dev)
+    f = lambda n: torch.empty(n, device=dev)
+    tg, td, rho, sp, tp = f(N), f(N), f(N), f(N), f(cfg.B)
+
+    def step():
+        b.retrace_targets(lp, lm, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"], target=tg, td=td, rho=rho)
+        b.compute_priorities(td, rho, ent, off, cfg.w, step_prio=sp, traj_prio=tp)
+    elapsed, ms = _timed(torch, step, args.steps, args.warmup)
+    alg_bytes = N * (20 + 12) + N * (12 + 4) + cfg.B * 12     # retrace: 5 in + 3 out; priorities: 3 in + 1 out
+    print(json.dumps({
+        "metric": "trajectory-steps/sec through Retrace + priorities (no logits) + % peak HBM GB/s",
+        "value": N * args.steps / elapsed, "unit": "trajectory-steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": cfg.B, "traj_steps": N,
+                   "gamma": cfg.gamma, "lambda": cfg.lam},
+        "roofline": {"bound": "hbm", "kernel": "k_retrace + k_priorities (two launches; launch-latency bound)",
+                     "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
+
+
+def bench_replay(args, b, torch, synth, dev):
+    """One step = sample K indices, recompute their priorities, scatter, rebuild the index (config 4)."""
+    cfg = synth.CONFIGS[4]
+    seed = synth.BASE_SEED + cfg.index
+    M, K = cfg.M, cfg.K
+    w = torch.zeros(M, device=dev)
+    ws = b.Workspace(M, device=dev)
+    p0 = synth.replay_priorities(M, cfg.replay, seed + 5, dev)
+    for s0 in range(0, M, 1 << 22):
+        b.update_priorities(w, torch.arange(s0, min(M, s0 + (1 << 22)), device=dev), p0[s0:s0 + (1 << 22)], cfg.alpha, ws)
+    total = args.steps + args.warmup
+    uni = synth.uniforms(K * total, seed + 6, dev).view(total, K)
+    prio = synth.td_errors(K * total, seed + 7, dev).abs().view(total, K)
+    idx = torch.empty(K, dtype=torch.int64, device=dev)
+    it = [0]
+
+    def step():
+        i = it[0] % total
+        it[0] += 1
+        b.sample_prioritized(w, uni[i], ws, idx, None)
+        b.update_priorities(w, idx, prio[i], cfg.alpha, ws)
+    elapsed, ms = _timed(torch, step, args.steps, args.warmup)
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0, f"status flags {st.flags:#x} rc {rc}"
+    # per step: two sweeps of the weights (maximum, integer block sums) and the index written once;
+    # per draw one 1 KB block of weights (the 4 KB of index entries it consults stay in cache) and
+    # 16 B of I/O; per update 12 B in and one 64-byte sector read-modify-written
+    alg_bytes = 2 * M * 4 + (M // 256) * 8 + K * (1024 + 8 + 8) + K * (8 + 4 + 64)
+    print(json.dumps({
+        "metric": "prioritized draws/sec incl. priority update and index rebuild + % peak HBM GB/s",
+        "value": K * args.steps / elapsed, "unit": "draws/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} (config {cfg.index})", "replay_entries": M, "draws": K, "alpha": cfg.alpha},
+        "roofline": {"bound": "hbm", "kernel": "k_sample + k_update_tag/commit + k_weight_max + k_super_sums + k_prefix_super",
+                     "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,9 +166,11 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = learner batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the CPU sample")
-    ap.add_argument("--path", choices=["scoring", "actor_grad"], default="scoring",
-                    help="scoring: the five-call hot path (default). actor_grad: the actor loss and its logit "
-                         "gradient (eq. (1)), the second sweep over the same logits")
+    ap.add_argument("--path", choices=["scoring", "actor_grad", "retrace", "replay"], default="scoring",
+                    help="scoring: the five-call hot path on the learner batch (default). actor_grad: the actor "
+                         "loss and its logit gradient (eq. (1)), the second sweep over the same logits. "
+                         "retrace: retrace_targets + compute_priorities on the long-scan workload (config 3). "
+                         "replay: sample + update + index rebuild on the 2^24-entry buffer (config 4)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()
@@ -99,6 +187,10 @@ def main():
     b.lib()   # fail loudly if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.path == "retrace":
+        return bench_retrace(args, b, torch, synth, dev)
+    if args.path == "replay":
+        return bench_replay(args, b, torch, synth, dev)
     cfg = synth.CONFIGS[args.config]
     assert cfg.V > 0 and cfg.M > 0, "bench runs a workload with logits and a replay buffer"
     seed = synth.BASE_SEED + cfg.index

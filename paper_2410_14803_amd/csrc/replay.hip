@@ -186,9 +186,7 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
     __shared__ uint32_t wave_best[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sblk = blockIdx.x;
-    const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
-    const int e = wb ? exponent_of(wb) : 0;
-    float4 v[16];
+    float4 v[16];   // requested before the maximum is reduced, so the two latencies overlap
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         const int blk = sblk * kSuperBlocks + wave * 16 + j;
@@ -201,13 +199,32 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
             if (base + 2 < M) v[j].z = weights[base + 2];
         }
     }
+    const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
+    const int e = wb ? exponent_of(wb) : 0;
+    // Sixteen wave-wide sums at once: in each of four exchange rounds a lane hands half of its
+    // partial sums to the partner lane and keeps the other half, so the number of live values
+    // halves while the number of lanes sharing each doubles (17 exchanges instead of 96).
+    // Afterwards lane L holds the sum of block L >> 2.
+    unsigned long long part[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-        unsigned long long q = 0ull;
-        if (wb != 0u) q = quantise(v[j].x, e) + quantise(v[j].y, e) + quantise(v[j].z, e) + quantise(v[j].w, e);
-        q = wave_sum_u64(q);
-        if (lane == 0) sums[wave * 16 + j] = q;
+        part[j] = 0ull;
+        if (wb != 0u) part[j] = quantise(v[j].x, e) + quantise(v[j].y, e) + quantise(v[j].z, e) + quantise(v[j].w, e);
     }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int half = 8 >> s, mask = 32 >> s;
+        const bool upper = (lane & mask) != 0;
+#pragma unroll
+        for (int i = 0; i < half; ++i) {
+            const unsigned long long keep = upper ? part[i + half] : part[i];
+            const unsigned long long send = upper ? part[i] : part[i + half];
+            part[i] = keep + __shfl_xor(send, mask, kWave);
+        }
+    }
+    part[0] += __shfl_xor(part[0], 2, kWave);
+    part[0] += __shfl_xor(part[0], 1, kWave);
+    if ((lane & 3) == 0) sums[wave * 16 + (lane >> 2)] = part[0];
     __syncthreads();
     unsigned long long total = 0ull;
     const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
