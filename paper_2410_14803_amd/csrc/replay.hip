@@ -396,90 +396,111 @@ __global__ __launch_bounds__(1024) void k_update_small(
     }
 }
 
-// Number of entries of a non-decreasing run of 256 u64 values that are <= t, i.e. the index of
-// the first entry > t.  Lane l holds entries 4l .. 4l+3.
-__device__ __forceinline__ int count_le(const unsigned long long (&c)[4], unsigned long long t) {
-    return __popcll(__ballot(c[0] <= t)) + __popcll(__ballot(c[1] <= t)) +
-           __popcll(__ballot(c[2] <= t)) + __popcll(__ballot(c[3] <= t));
+// Sampling: a draw is served by a group of 16 lanes, four draws per wave.  Each level of the
+// index is a non-decreasing run of 256 u64 values searched 16-ary in two probes: lane g of the
+// group first reads the last entry of the g-th run of 16 and the group counts (ballot +
+// popcount) how many are <= t, which selects a run; then the lanes read that run's 16 entries
+// and count again.  The entry just before the hit -- the mass to subtract -- is already in a
+// register of some lane of the group and is fetched with a shuffle.
+__device__ __forceinline__ int group_count(bool pred, int group) {
+    return __popc((uint32_t)((__ballot(pred) >> (16 * group)) & 0xFFFFull));
 }
 
-// One wave per draw.  (Serving four draws per wave level by level, to overlap their dependent
-// reads, was measured at twice the time: the kernel is bound by instruction issue -- the u64
-// shuffle scan and the quantisation -- not by latency.)
+// Rank of t in the 256-entry run `run` (entries at index >= limit count as +inf), and the entry
+// just before that rank (0 for rank 0).  All 16 lanes of a group pass the same t.
+__device__ __forceinline__ int search256(const unsigned long long* __restrict__ run, int limit,
+                                         unsigned long long t, int group, int gl, unsigned long long& before) {
+    const int ia = 16 * gl + 15;
+    const unsigned long long va = ia < limit ? run[ia] : ~0ull;
+    const int chunk = group_count(va <= t, group);                 // 0..16
+    const int ib = 16 * min(chunk, 15) + gl;
+    const unsigned long long vb = (chunk < 16 && ib < limit) ? run[ib] : ~0ull;
+    const int within = group_count(vb <= t, group);                // 0..15 when chunk < 16
+    const unsigned long long prev_b = __shfl(vb, 16 * group + max(within - 1, 0), kWave);
+    const unsigned long long prev_a = __shfl(va, 16 * group + max(chunk - 1, 0), kWave);
+    before = within > 0 ? prev_b : (chunk > 0 ? prev_a : 0ull);
+    return chunk < 16 ? 16 * chunk + within : 256;
+}
+
 __global__ __launch_bounds__(256) void k_sample(
     const float* __restrict__ weights, long long M, const WsHeader* __restrict__ hdr,
     const unsigned long long* __restrict__ block_cum, int nblk,
     const unsigned long long* __restrict__ super_cum, const double* __restrict__ uniforms,
     int K, long long* __restrict__ idx_out, float* __restrict__ prob_out, uint32_t* __restrict__ flags) {
-    const int lane = threadIdx.x & 63;
-    const int k = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (k >= K) return;
+    const int lane = threadIdx.x & 63, group = lane >> 4, gl = lane & 15;
+    const int wave_id = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (wave_id * 4 >= K) return;                    // whole waves leave together
+    const int k = wave_id * 4 + group;
+    const bool live = k < K;                         // dead groups run along on draw K-1 and store nothing
+    const int kk = live ? k : K - 1;
     const unsigned long long total = hdr->total;
     if (total == 0ull) {
-        if (lane == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
+        if (live && gl == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
         return;
     }
-    double u = uniforms[k];
-    if (!(u >= 0.0)) { u = 0.0; if (lane == 0) atomicOr(flags, 0x10u); }
+    double u = uniforms[kk];
+    if (!(u >= 0.0)) { u = 0.0; if (live && gl == 0) atomicOr(flags, 0x10u); }
     // one rounding for the conversion, one for the product, then truncation
     const double prod = __dmul_rn(u, __ull2double_rn(total));
     unsigned long long t = (prod >= 18446744073709551616.0) ? total - 1 : (unsigned long long)prod;
     if (t > total - 1) t = total - 1;
 
     // level 1: first super-block whose inclusive prefix exceeds t (the padding equals Total > t)
-    unsigned long long c[4];
-    {
-        const ulonglong2 a = *reinterpret_cast<const ulonglong2*>(super_cum + 4 * lane);
-        const ulonglong2 b = *reinterpret_cast<const ulonglong2*>(super_cum + 4 * lane + 2);
-        c[0] = a.x; c[1] = a.y; c[2] = b.x; c[3] = b.y;
-    }
-    const int sblk = count_le(c, t);
-    unsigned long long rem = t - (sblk ? super_cum[sblk - 1] : 0ull);
+    unsigned long long before;
+    const int sblk = search256(super_cum, kSuperBlocks, t, group, gl, before);
+    bool stale = sblk >= kSuperBlocks;               // cannot happen with a current index
+    unsigned long long rem = t - (stale ? 0ull : before);
     // level 2: first block of that super-block whose inclusive prefix exceeds the remainder
-    const int first = sblk * kSuperBlocks;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int blk = first + 4 * lane + j;
-        c[j] = blk < nblk ? block_cum[blk] : ~0ull;
-    }
-    const int within = count_le(c, rem);
-    const int blk = first + within;
-    // a stale index (weights changed without a rebuild) can run past the end: report -1
-    if (sblk >= kSuperBlocks || within >= kSuperBlocks || blk >= nblk) {
-        if (lane == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
-        return;
-    }
-    rem -= within ? block_cum[blk - 1] : 0ull;
+    const int first = (stale ? 0 : sblk) * kSuperBlocks;
+    const int within = search256(block_cum + first, nblk - first, rem, group, gl, before);
+    stale = stale || within >= kSuperBlocks || first + within >= nblk;
+    const int blk = stale ? 0 : first + within;
+    rem -= stale ? 0ull : before;
 
-    // level 3: scan the block's 256 weights
+    // level 3: the block's 256 weights, 16 consecutive ones per lane
     const int e = exponent_of(hdr->wmax_bits);
-    const long long base = (long long)blk * kReplayBlock + lane * 4;
-    unsigned long long qv[4] = {0ull, 0ull, 0ull, 0ull};
-    if (base + 3 < M) {
-        const float4 v = *reinterpret_cast<const float4*>(weights + base);
-        qv[0] = quantise(v.x, e); qv[1] = quantise(v.y, e); qv[2] = quantise(v.z, e); qv[3] = quantise(v.w, e);
-    } else {
-        for (int j = 0; j < 4; ++j) if (base + j < M) qv[j] = quantise(weights[base + j], e);
+    const long long base = (long long)blk * kReplayBlock + gl * 16;
+    unsigned long long q[16];
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) {
+        const long long b4 = base + 4 * v4;
+        float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (b4 + 3 < M) w = *reinterpret_cast<const float4*>(weights + b4);
+        else if (b4 < M) {
+            w.x = weights[b4];
+            if (b4 + 1 < M) w.y = weights[b4 + 1];
+            if (b4 + 2 < M) w.z = weights[b4 + 2];
+        }
+        q[4 * v4 + 0] = quantise(w.x, e); q[4 * v4 + 1] = quantise(w.y, e);
+        q[4 * v4 + 2] = quantise(w.z, e); q[4 * v4 + 3] = quantise(w.w, e);
     }
-    const unsigned long long mine = qv[0] + qv[1] + qv[2] + qv[3];
+    unsigned long long mine = 0ull;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) mine += q[j];
     unsigned long long incl = mine;
 #pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        unsigned long long up = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += up;
+    for (int d = 1; d < 16; d <<= 1) {               // inclusive scan inside the group of 16 lanes
+        const unsigned long long up = __shfl_up(incl, d, 16);
+        if (gl >= d) incl += up;
     }
-    const unsigned long long hit = __ballot(incl > rem);
-    if (hit == 0ull) {   // stale index again
-        if (lane == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
-        return;
-    }
-    const int owner = __ffsll((long long)hit) - 1;
-    if (lane == owner) {
-        unsigned long long cc = incl - mine;
+    const int owner = group_count(incl <= rem, group);   // lanes whose running total has not passed rem yet
+    // a stale index (weights changed without a rebuild) can run past the end: report -1
+    if (stale || owner >= 16) {
+        if (live && gl == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
+    } else if (live && gl == owner) {
+        unsigned long long c = incl - mine;
         int j = 0;
-        for (; j < 3; ++j) { if (cc + qv[j] > rem) break; cc += qv[j]; }
+#pragma unroll
+        for (int i = 0; i < 15; ++i) {
+            const bool pass = (j == i) && (c + q[i] <= rem);
+            c += pass ? q[i] : 0ull;
+            j += pass ? 1 : 0;
+        }
+        unsigned long long qj = q[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) qj = (j == i) ? q[i] : qj;
         idx_out[k] = base + j;
-        if (prob_out) prob_out[k] = (float)((double)qv[j] / (double)total);
+        if (prob_out) prob_out[k] = (float)((double)qj / (double)total);
     }
 }
 
@@ -529,7 +550,8 @@ hipError_t sample_launch(const float* weights, long long M, const WsHeader* hdr,
                          const double* uniforms, int K, long long* idx_out, float* prob_out,
                          uint32_t* flags, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
-    const unsigned g = (unsigned)(((long long)K * kWave + 255) / 256);
+    const long long waves = ((long long)K + 3) / 4;      // four draws per wave
+    const unsigned g = (unsigned)((waves * kWave + 255) / 256);
     hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, hdr, block_cum, nblk, super_cum,
                        uniforms, K, idx_out, prob_out, flags);
     return hipGetLastError();
