@@ -13,7 +13,9 @@
 //    so the rescale branch is almost never taken; the exact running maximum is kept
 //    separately and all lanes are brought to the common reference once at the end.
 //  * logp = ln2*(x_tok*log2e - K) - ln S  and  H = ln S - ln2*T/S  hold for any common
-//    reference K, so rounding in K cancels.
+//    reference K, so rounding in K cancels; and because x*log2e - k is one fused
+//    multiply-add (exact product, one rounding of the small result) the accuracy does not
+//    depend on how large the logits themselves are.
 //  * Per element: 1 unpack, 1/2 max3, 1/2 min3, 1 fma, 1 exp2, 1 add, 1 fma.
 #include "aride_device.h"
 

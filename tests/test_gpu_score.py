@@ -194,3 +194,19 @@ def test_nonfinite_values_propagate():
     assert got["tok_logp"][1] == -np.inf and np.isnan(got["tok_logp"][6])
     assert got["step_logp"][0] == -np.inf and np.isnan(got["step_logp"][1])
     assert np.isfinite(got["tok_ent"][1]) and np.isnan(got["step_ent"][1])
+
+
+@pytest.mark.parametrize("offset", [-20480.0, -512.0, 768.0, 24576.0])
+def test_accuracy_does_not_depend_on_the_logits_magnitude(oracle, offset):
+    # softmax is shift invariant; differences of bf16 values are exact in fp32, so a common
+    # offset of any size must not cost accuracy (values are kept exactly representable in bf16)
+    V, A = 5000, 2
+    g = torch.Generator(device=DEV); g.manual_seed(3)
+    step = 2.0 ** (int(np.floor(np.log2(abs(offset)))) - 7)           # bf16 spacing in offset's binade
+    x = torch.randint(-30, 31, (8, V), generator=g, device=DEV).float() * step + offset   # stays below the next binade
+    logits = x.to(torch.bfloat16)
+    assert torch.equal(logits.float(), x)
+    tokens = synth.action_tokens(logits, seed=4)
+    got, _ = run_gpu(logits, tokens, A)
+    want = oracle.score_logits(bits_of(logits), npf(tokens), A)
+    compare(got, want, V, A, f"offset {offset}")
