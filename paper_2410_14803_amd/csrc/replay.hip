@@ -186,7 +186,9 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
     __shared__ uint32_t wave_best[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sblk = blockIdx.x;
-    float4 v[16];   // requested before the maximum is reduced, so the two latencies overlap
+    const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
+    const int e = wb ? exponent_of(wb) : 0;
+    float4 v[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         const int blk = sblk * kSuperBlocks + wave * 16 + j;
@@ -199,32 +201,34 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
             if (base + 2 < M) v[j].z = weights[base + 2];
         }
     }
-    const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
-    const int e = wb ? exponent_of(wb) : 0;
-    // Sixteen wave-wide sums at once: in each of four exchange rounds a lane hands half of its
-    // partial sums to the partner lane and keeps the other half, so the number of live values
-    // halves while the number of lanes sharing each doubles (17 exchanges instead of 96).
-    // Afterwards lane L holds the sum of block L >> 2.
-    unsigned long long part[16];
+    // Four wave-wide sums at a time, so that a wave starts reducing as soon as its first four
+    // loads are back while the rest are still in flight.  In each of two exchange rounds a lane
+    // hands half of its partial sums to the partner lane and keeps the other half (the number
+    // of live values halves, the number of lanes sharing each doubles); four more rounds finish
+    // the one value left.  Afterwards lane L holds the sum of block 4g + (L >> 4).
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        part[j] = 0ull;
-        if (wb != 0u) part[j] = quantise(v[j].x, e) + quantise(v[j].y, e) + quantise(v[j].z, e) + quantise(v[j].w, e);
-    }
+    for (int g = 0; g < 4; ++g) {
+        unsigned long long part[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int half = 8 >> s, mask = 32 >> s;
-        const bool upper = (lane & mask) != 0;
-#pragma unroll
-        for (int i = 0; i < half; ++i) {
-            const unsigned long long keep = upper ? part[i + half] : part[i];
-            const unsigned long long send = upper ? part[i] : part[i + half];
-            part[i] = keep + __shfl_xor(send, mask, kWave);
+        for (int j = 0; j < 4; ++j) {
+            const float4 w = v[4 * g + j];
+            part[j] = wb != 0u ? quantise(w.x, e) + quantise(w.y, e) + quantise(w.z, e) + quantise(w.w, e) : 0ull;
         }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int half = 2 >> s, mask = 32 >> s;
+            const bool upper = (lane & mask) != 0;
+#pragma unroll
+            for (int i = 0; i < half; ++i) {
+                const unsigned long long keep = upper ? part[i + half] : part[i];
+                const unsigned long long send = upper ? part[i] : part[i + half];
+                part[i] = keep + __shfl_xor(send, mask, kWave);
+            }
+        }
+#pragma unroll
+        for (int d = 8; d >= 1; d >>= 1) part[0] += __shfl_xor(part[0], d, kWave);
+        if ((lane & 15) == 0) sums[wave * 16 + 4 * g + (lane >> 4)] = part[0];
     }
-    part[0] += __shfl_xor(part[0], 2, kWave);
-    part[0] += __shfl_xor(part[0], 1, kWave);
-    if ((lane & 3) == 0) sums[wave * 16 + (lane >> 2)] = part[0];
     __syncthreads();
     unsigned long long total = 0ull;
     const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
