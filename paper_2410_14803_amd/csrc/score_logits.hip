@@ -4,8 +4,10 @@
 //
 // Design for gfx950:
 //  * HBM-bound streaming reduction; nothing here is a contraction, so no MFMA.
-//  * One row is swept by WPR waves (1, 2 or 4); each lane issues 16-byte loads
-//    (8 bf16), UNROLL of them back to back so several KB per wave are in flight.
+//  * One wave sweeps one row; each lane issues 16-byte loads (8 bf16), UNROLL of them back
+//    to back, so 4 KB per wave are in flight.  Spreading a row over 2 or 4 waves, prefetching
+//    the next batch before reducing the current one, or other workgroup sizes were measured
+//    and change nothing: the kernel runs at the rate of a pure read probe.
 //  * Every logit is read once.  Each lane keeps an online log-sum-exp state in base-2
 //    units against a lazily updated reference k (k = ref*log2e):
 //        s = sum 2^(x*log2e - k),   t = sum 2^(x*log2e - k) * (x*log2e - k)
@@ -22,17 +24,11 @@
 namespace aride {
 
 // Tuning parameters (the defaults are the measured best on MI355X for V = 32128 .. 151936).
-#ifndef ARIDE_SCORE_WPR
-#define ARIDE_SCORE_WPR 1       // waves per logit row (1, 2 or 4)
-#endif
 #ifndef ARIDE_SCORE_UNROLL
 #define ARIDE_SCORE_UNROLL 4    // 16-byte loads in flight per lane and batch
 #endif
-#ifndef ARIDE_SCORE_PIPELINE
-#define ARIDE_SCORE_PIPELINE 0  // 1: issue the next batch of loads before reducing the current one
-#endif
 #ifndef ARIDE_SCORE_WAVES
-#define ARIDE_SCORE_WAVES 4     // waves per workgroup (a multiple of ARIDE_SCORE_WPR)
+#define ARIDE_SCORE_WAVES 4     // waves (= rows) per workgroup
 #endif
 #ifndef ARIDE_SCORE_NT
 #define ARIDE_SCORE_NT 1        // 1: non-temporal loads
@@ -134,32 +130,25 @@ __device__ __forceinline__ void to_common(float negk, float s, float t, float kc
     to = (s != 0.f) ? r * fmaf(d, s, t) : 0.f;
 }
 
-template <int WPR, int UNROLL>
+template <int UNROLL>
 __global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
     const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
-    constexpr int kRowsPerBlock = ARIDE_SCORE_WAVES / WPR;
-    constexpr int kTPR = kWave * WPR;  // threads per row
-    __shared__ float sh[WPR > 1 ? ARIDE_SCORE_WAVES * 3 : 1];
-
-    const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
-    const long long row = (long long)blockIdx.x * kRowsPerBlock + wave / WPR;
-    const int sub = wave % WPR;         // which wave of the row
-    const int l = sub * kWave + lane;   // thread index within the row
-    const bool row_ok = row < R;
+    const long long row = (long long)blockIdx.x * ARIDE_SCORE_WAVES + (threadIdx.x >> 6);
+    if (row >= R) return;   // whole waves leave together; the kernel has no workgroup barrier
 
-    int tok = row_ok ? tokens[row] : -1;
-    const bool live = row_ok && tok >= 0 && tok < V;
-    if (row_ok && tok >= V && l == 0) atomicOr(status, 0x1u);
+    const int tok = tokens[row];
+    const bool live = tok >= 0 && tok < V;
+    if (tok >= V && lane == 0) atomicOr(status, 0x1u);
 
     LaneState a;
     lane_init(a);
     float xtok = 0.f;
     if (live) {
         const uint16_t* p = logits + row * row_stride;
-        if (l == 0) xtok = bits_to_float(((uint32_t)p[tok]) << 16);
+        if (lane == 0) xtok = bits_to_float(((uint32_t)p[tok]) << 16);
         // Elements before the first 16-byte boundary, the aligned 8-element vectors, the rest.
         int head = (int)(((16u - (uint32_t)((uintptr_t)p & 15u)) & 15u) >> 1);
         if (head > V) head = V;
@@ -167,85 +156,45 @@ __global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
         const int tail0 = head + (nvec << 3);
         const u32x4* pv = reinterpret_cast<const u32x4*>(p + head);
 
-        int i = l;
-        constexpr int kStride = UNROLL * kTPR;
-#if ARIDE_SCORE_PIPELINE
-        // software pipeline: the next batch of loads is issued before the current one is reduced
-        if (i + (UNROLL - 1) * kTPR < nvec) {
-            u32x4 cur[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) cur[u] = load16(pv + i + u * kTPR);
-            i += kStride;
-            while (i + (UNROLL - 1) * kTPR < nvec) {
-                u32x4 nxt[UNROLL];
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u) nxt[u] = load16(pv + i + u * kTPR);
-                accumulate_batch<UNROLL>(a, cur);
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
-                i += kStride;
-            }
-            accumulate_batch<UNROLL>(a, cur);
-        }
-#else
-        for (; i + (UNROLL - 1) * kTPR < nvec; i += kStride) {
+        int i = lane;
+        for (; i + (UNROLL - 1) * kWave < nvec; i += UNROLL * kWave) {
             u32x4 v[UNROLL];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) v[u] = load16(pv + i + u * kTPR);
+            for (int u = 0; u < UNROLL; ++u) v[u] = load16(pv + i + u * kWave);
             accumulate_batch<UNROLL>(a, v);
         }
-#endif
-        for (; i < nvec; i += kTPR) {
+        for (; i < nvec; i += kWave) {
             u32x4 v[1] = {load16(pv + i)};
             accumulate_batch<1>(a, v);
         }
-        if (l < head) {
-            float x[1] = {bits_to_float(((uint32_t)p[l]) << 16)};
+        if (lane < head) {
+            float x[1] = {bits_to_float(((uint32_t)p[lane]) << 16)};
             lane_accumulate<1>(a, x);
         }
-        if (tail0 + l < V) {   // fewer than 8 elements remain
-            float x[1] = {bits_to_float(((uint32_t)p[tail0 + l]) << 16)};
+        if (tail0 + lane < V) {   // fewer than 8 elements remain
+            float x[1] = {bits_to_float(((uint32_t)p[tail0 + lane]) << 16)};
             lane_accumulate<1>(a, x);
         }
     }
 
-    // Wave-level merge: common reference = exact wave maximum.
-    float M = wave_max(a.mx);
-    float kc = M * kLog2e;
+    // Merge the 64 lane states: common reference = exact row maximum (in log2 units).
+    const float M = wave_max(a.mx);
+    const float kc = M * kLog2e;
     float s, t;
     to_common(a.negk, a.s0 + a.s1, a.t0 + a.t1, kc, s, t);
     s = wave_sum(s);
     t = wave_sum(t);
 
-    if constexpr (WPR > 1) {
-        if (lane == 0) { sh[wave * 3 + 0] = M; sh[wave * 3 + 1] = s; sh[wave * 3 + 2] = t; }
-        __syncthreads();
-        const int w0 = (wave / WPR) * WPR;
-        float Mb = sh[w0 * 3];
-#pragma unroll
-        for (int w = 1; w < WPR; ++w) Mb = fmaxf(Mb, sh[(w0 + w) * 3]);
-        float kb = Mb * kLog2e;
-        float S = 0.f, T = 0.f;
-#pragma unroll
-        for (int w = 0; w < WPR; ++w) {
-            float so, to;
-            to_common(-(sh[(w0 + w) * 3] * kLog2e), sh[(w0 + w) * 3 + 1], sh[(w0 + w) * 3 + 2], kb, so, to);
-            S += so; T += to;
-        }
-        s = S; t = T; kc = kb;
-    }
-
-    if (row_ok && l == 0) {
+    if (lane == 0) {
         float lp = 0.f, en = 0.f;
         if (live) {
-            float logS = logf(s);
+            const float logS = logf(s);
             lp = kLn2 * fmaf(xtok, kLog2e, -kc) - logS;
             en = logS - kLn2 * t / s;
         }
         if (tok_logp) tok_logp[row] = lp;
         if (tok_ent) tok_ent[row] = en;
     }
-
 }
 
 // Per-step sums of the A per-token values: one wave per step, lanes stride over the step's
@@ -275,23 +224,14 @@ __global__ __launch_bounds__(256) void k_step_sums(
     }
 }
 
-template <int WPR, int UNROLL>
-static hipError_t launch_rows(const uint16_t* logits, long long R, int V, long long stride,
-                              const int* tokens, float* tl, float* te, uint32_t* status,
-                              hipStream_t st) {
-    constexpr int rpb = ARIDE_SCORE_WAVES / WPR;
-    long long blocks = (R + rpb - 1) / rpb;
-    hipLaunchKernelGGL((k_score_rows<WPR, UNROLL>), dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES), 0, st,
-                       logits, R, V, stride, tokens, tl, te, status);
-    return hipGetLastError();
-}
-
 // Row sweep, then (when a per-step output is wanted) the per-step sums of the per-token arrays.
 hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long long stride,
                                const int* tokens, int A, float* tok_logp, float* tok_ent,
                                float* step_logp, float* step_ent, uint32_t* status, hipStream_t st) {
-    hipError_t err = launch_rows<ARIDE_SCORE_WPR, ARIDE_SCORE_UNROLL>(logits, R, V, stride, tokens, tok_logp,
-                                                                      tok_ent, status, st);
+    const long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
+    hipLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES), 0,
+                       st, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
+    hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!step_logp && !step_ent)) return err;
     const long long N = R / A;
     hipLaunchKernelGGL(k_step_sums, dim3((unsigned)((N * kWave + 255) / 256)), dim3(256), 0, st,

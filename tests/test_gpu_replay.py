@@ -240,3 +240,34 @@ def test_insert_then_sample_then_update_cycle(oracle):
         torch.cuda.synchronize()
         wo = npf(w).copy()          # continue from the device's weight bits
     assert cursor == (8 * 700) % M
+
+
+def test_many_super_blocks_with_a_ragged_tail(oracle):
+    # 65 super-blocks (the one-workgroup-per-super-block path) and a last block of 9 weights
+    M = 64 * 65536 + 3 * 256 + 9
+    w = fresh(M, "lognormal", 41, 0.6, oracle)
+    w[torch.arange(0, M, 5, device=DEV)] = 0.0
+    ws = b.Workspace(M)
+    b.update_priorities(w, None, None, 0.6, ws)
+    u = synth.uniforms(4000, 42, DEV)
+    u[:3] = torch.tensor([0.0, np.nextafter(1.0, 0.0), 1.0 - 2.0 ** -30], dtype=torch.float64)
+    check_sample(oracle, w, u, ws, "65 super-blocks")
+    st, rc = ws.status()
+    q, total = oracle.quantise_weights(npf(w))
+    assert rc == b.OK and st.total == total
+
+
+def test_heavy_duplicates_in_a_large_batch(oracle):
+    # K above the single-workgroup scatter limit: the two-kernel tag/commit path, every index repeated ~400 times
+    M, K = 100000, 20000
+    w = fresh(M, "exp", 43, 0.6, oracle)
+    ws = b.Workspace(M)
+    g = torch.Generator(device=DEV); g.manual_seed(44)
+    idx = torch.randint(0, 50, (K,), generator=g, device=DEV) * 1999
+    prio = torch.rand(K, generator=g, device=DEV) * 3
+    wo = npf(w).copy()
+    b.update_priorities(w, idx, prio, 0.6, ws)
+    torch.cuda.synchronize()
+    oracle.update_priorities(wo, npf(idx), npf(prio), 0.6)
+    np.testing.assert_allclose(npf(w), wo, rtol=1e-6, atol=0)
+    check_sample(oracle, w, synth.uniforms(2000, 45, DEV), ws, "heavy duplicates, large batch")
