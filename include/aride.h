@@ -97,7 +97,8 @@ int aride_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Copies the status block to host memory `out` and waits for `stream`.  Returns
- * ARIDE_E_ZERO_MASS when the ZERO_MASS bit is set, else ARIDE_OK.
+ * ARIDE_E_ZERO_MASS when the index as last rebuilt has no mass (total == 0), else ARIDE_OK.
+ * The bits of `flags` are sticky: they accumulate until aride_workspace_init.
  */
 int aride_status_read(const void* ws, aride_status* out /* host */, void* stream);
 

@@ -65,7 +65,8 @@ int aride_status_read(const void* ws, aride_status* out, void* stream) {
     if (hipMemcpyAsync(out, ws, sizeof(aride_status), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
         return ARIDE_E_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ARIDE_E_HIP;
-    return (out->flags & ARIDE_ST_ZERO_MASS) ? ARIDE_E_ZERO_MASS : ARIDE_OK;
+    // the flag is sticky; the error reports the state of the index as it stands now
+    return ((out->flags & ARIDE_ST_ZERO_MASS) && out->total == 0) ? ARIDE_E_ZERO_MASS : ARIDE_OK;
 }
 
 int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,

@@ -114,6 +114,12 @@ def test_zero_mass_and_bad_weights(oracle):
     st, rc = ws.status()
     assert rc == b.E_ZERO_MASS and st.flags & b.ST_ZERO_MASS and st.total == 0
     assert np.all(idx == -1) and np.all(prob == 0)
+    w[17] = 2.5                                   # mass returns: the error goes away, the sticky bit stays
+    b.update_priorities(w, None, None, 0.6, ws)
+    idx, prob = gpu_sample(w, synth.uniforms(10, 1, DEV), ws)
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags & b.ST_ZERO_MASS and st.total > 0
+    assert np.all(idx == 17) and np.all(prob == 1.0)
 
     ws = b.Workspace(M)
     w = fresh(M, "exp", 2, 0.6, oracle)
