@@ -1,0 +1,140 @@
+"""Seeded random shapes for every entry point: many small cases with odd sizes, strides,
+masks and length mixes, each compared with the oracle to the bars of tests/_util.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_14803_amd import binding as b
+from paper_2410_14803_amd import synth
+from _util import assert_close, bits_of, ent_floor, npf
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def test_score_and_actor_grad_random_shapes(oracle):
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        A = int(rng.integers(1, 9))
+        N = int(rng.integers(1, 7))
+        V = int(rng.choice([1, 2, 3, 9, 17, 63, 64, 65, 127, 255, 257, 511, 1000, 1023, 1025, 4097, 9000]))
+        pad = int(rng.integers(0, 9))
+        R = N * A
+        print(f"case {case}: N={N} A={A} V={V} pad={pad}", flush=True)
+        logits = synth.logits_bf16(R, V + pad, seed=1000 + case, device=DEV, heavy_tail=bool(case % 2))
+        tokens = synth.action_tokens(logits[:, :V].contiguous(), seed=2000 + case)
+        mask = torch.as_tensor(rng.random(R) < 0.15, device=DEV)
+        tokens[mask] = -1
+        ws = b.Workspace(0)
+        f = lambda n: torch.empty(n, device=DEV)
+        tl, te, sl, se = f(R), f(R), f(N), f(N)
+        b.score_logits(logits, tokens, A, ws, tok_logp=tl, tok_ent=te, step_logp=sl, step_ent=se, V=V)
+        want = oracle.score_logits(bits_of(logits), npf(tokens), A, V=V)
+        Vf = max(V, 2)
+        assert_close(npf(tl), want["tok_logp"], 1.0, "tok_logp")
+        assert_close(npf(te), want["tok_ent"], ent_floor(Vf), "tok_ent")
+        assert_close(npf(sl), want["step_logp"], 1.0, "step_logp")
+        assert_close(npf(se), want["step_ent"], ent_floor(Vf), "step_ent")
+        # gradient (fp32 output) on the same rows
+        rho = torch.as_tensor(np.exp(rng.standard_normal(N) * 0.4).astype(np.float32), device=DEV)
+        tgt = torch.as_tensor(rng.uniform(-1, 1, N).astype(np.float32), device=DEV)
+        base = torch.as_tensor(rng.uniform(-1, 1, N).astype(np.float32), device=DEV)
+        beta, scale = float(rng.choice([0.0, 0.01, 0.3])), 1.0 / N
+        g32 = torch.zeros((R, V + pad), device=DEV)
+        loss = torch.zeros(1, device=DEV)
+        b.actor_loss_grad(logits, tokens, A, tl, te, sl, se, rho, tgt, base, beta, scale, grad=g32, loss=loss, V=V)
+        torch.cuda.synchronize()
+        o_loss, o_grad = oracle.actor_loss_grad(bits_of(logits), npf(tokens), A, npf(rho), npf(tgt), npf(base), beta,
+                                                scale, V=V)
+        coef = np.repeat(np.abs(npf(rho).astype(np.float64) * (npf(tgt).astype(np.float64) - npf(base))), A)
+        floor = 1e-2 * scale * (coef + beta * (1.0 + want["tok_ent"]))
+        err = np.abs(npf(g32)[:, :V] - o_grad)
+        assert np.all(err <= 1e-4 * np.maximum(np.abs(o_grad), floor[:, None]) + 1e-30), f"case {case}: gradient"
+        assert_close(npf(loss), [o_loss], 1.0, "loss")
+
+
+def test_retrace_random_length_mixes(oracle):
+    rng = np.random.default_rng(7)
+    cfg = synth.CONFIGS[3]
+    for case in range(25):
+        B = int(rng.integers(1, 40))
+        kind = case % 4
+        if kind == 0:
+            lens = rng.integers(0, 6, B)
+        elif kind == 1:
+            lens = rng.integers(1, 300, B)
+        elif kind == 2:
+            lens = rng.choice([0, 1, 63, 64, 65, 255, 256, 257, 511, 512, 513], B)
+        else:
+            lens = np.concatenate([rng.integers(1, 30, B - 1), [int(rng.integers(1000, 5000))]])
+        print(f"case {case}: B={B} N={int(lens.sum())}", flush=True)
+        off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        N = int(off_np[-1])
+        off = torch.as_tensor(off_np, device=DEV)
+        lp = synth.policy_logprobs(max(N, 1), 3000 + case, DEV)[:N].contiguous()
+        si = synth.step_inputs(cfg, off_np, 4000 + case, DEV)
+        lm = lp + si["mu_noise"]
+        boot = torch.as_tensor(rng.uniform(-1, 1, B).astype(np.float32), device=DEV)
+        gamma, lam = float(rng.choice([0.9, 0.99, 1.0])), float(rng.choice([0.0, 0.5, 0.95, 1.0]))
+        vtrace = bool(case % 3 == 0)
+        out = {k: torch.full((N,), 7.0, device=DEV) for k in ("target", "td", "rho")}
+        b.retrace_targets(lp, lm, si["reward"], si["value"], off, gamma, lam, q=si["q"], boot=boot, vtrace=vtrace,
+                          rho_bar=1.5, c_bar=0.9, **out)
+        sp, tp = torch.full((N,), 7.0, device=DEV), torch.full((B,), 7.0, device=DEV)
+        b.compute_priorities(out["td"], out["rho"], si["value"], off, (1.0, 0.5, 0.1), step_prio=sp, traj_prio=tp)
+        ret, lab = torch.full((N,), 7.0, device=DEV), torch.full((N,), 7.0, device=DEV)
+        b.mc_returns(si["reward"], off, gamma, ret=ret, label=lab)
+        torch.cuda.synchronize()
+        args = (npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, gamma, lam)
+        want = (oracle.vtrace_targets(*args, 1.5, 0.9, q=npf(si["q"]), boot=npf(boot)) if vtrace
+                else oracle.retrace_targets(*args, q=npf(si["q"]), boot=npf(boot)))
+        for k in ("target", "td", "rho"):
+            assert_close(npf(out[k]), want[k], 1.0, f"case {case} {k}")
+        wp = oracle.compute_priorities(npf(out["td"]), npf(out["rho"]), npf(si["value"]), off_np, 1.0, 0.5, 0.1)
+        assert_close(npf(sp), wp["step_prio"], 1.0, f"case {case} step_prio")
+        assert_close(npf(tp), wp["traj_prio"], 1.0, f"case {case} traj_prio")
+        o_ret, o_lab = oracle.mc_returns(npf(si["reward"]), off_np, gamma)
+        assert_close(npf(ret), o_ret, 1.0, f"case {case} mc return")
+        np.testing.assert_array_equal(npf(lab), o_lab)
+
+
+def test_replay_random_buffers(oracle):
+    rng = np.random.default_rng(11)
+    for case in range(25):
+        M = int(rng.choice([1, 7, 255, 256, 257, 3000, 8192, 8193, 65535, 65536, 65537, 200003]))
+        K = int(rng.choice([0, 1, 5, 300, 8192, 8193, 20000]))
+        alpha = float(rng.choice([0.0, 0.5, 0.6, 1.0]))
+        print(f"case {case}: M={M} K={K} alpha={alpha}", flush=True)
+        p = np.exp(rng.standard_normal(M) * rng.choice([0.5, 3.0, 12.0])).astype(np.float32)
+        p[rng.random(M) < rng.choice([0.0, 0.3, 0.9])] = 0.0
+        p[int(rng.integers(0, M))] = np.float32(1.5)            # at least one entry with mass
+        w_host = np.zeros(M, np.float32)
+        oracle.update_priorities(w_host, np.arange(M), p, alpha)
+        w = torch.as_tensor(w_host, device=DEV)
+        ws = b.Workspace(M)
+        idx = torch.as_tensor(rng.integers(0, M, K), device=DEV)
+        prio = torch.as_tensor(np.abs(rng.standard_normal(K)).astype(np.float32), device=DEV)
+        b.update_priorities(w, idx if K else None, prio if K else None, alpha, ws)
+        torch.cuda.synchronize()
+        oracle.update_priorities(w_host, npf(idx), npf(prio), alpha)
+        np.testing.assert_allclose(npf(w), w_host, rtol=1e-6, atol=0)
+        u = synth.uniforms(700, 5000 + case, DEV)
+        got = torch.empty(700, dtype=torch.int64, device=DEV)
+        prob = torch.empty(700, device=DEV)
+        b.sample_prioritized(w, u, ws, got, prob)
+        torch.cuda.synchronize()
+        oi, op, rc = oracle.sample_prioritized(npf(w), npf(u))
+        np.testing.assert_array_equal(npf(got), oi, err_msg=f"case {case}")
+        np.testing.assert_allclose(npf(prob), op.astype(np.float32), rtol=1e-6)
+        cur = int(rng.integers(0, M))
+        newp = torch.as_tensor(np.abs(rng.standard_normal(max(K, 1))).astype(np.float32) + 0.01, device=DEV)
+        w2 = npf(w).copy()
+        nc = b.replay_insert(w, cur, newp, alpha, ws)
+        oc, _ = oracle.replay_insert(w2, cur, npf(newp), alpha)
+        torch.cuda.synchronize()
+        assert nc == oc
+        np.testing.assert_allclose(npf(w), w2, rtol=1e-6)
+        b.sample_prioritized(w, u, ws, got, None)
+        torch.cuda.synchronize()
+        oi, _, _ = oracle.sample_prioritized(npf(w), npf(u))
+        np.testing.assert_array_equal(npf(got), oi, err_msg=f"case {case} after insert")
