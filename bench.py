@@ -60,6 +60,20 @@ def bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, ste
     ms = e0.elapsed_time(e1) / args.steps
     alg_bytes = R * cfg.V * 4 + R * 12 + N * 12     # logits in, bf16 gradient out, per-row and per-step scalars
     achieved = alg_bytes / (ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        h = lambda t: t.detach().cpu().numpy()
+        n_s = min(N, 8)                       # a few whole steps: the oracle's gradient is single-threaded
+        r_s = n_s * cfg.A
+        bits = logits[:r_s].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        oracle.actor_loss_grad(bits, h(tokens[:r_s]), cfg.A, h(rho[:n_s]), h(target[:n_s]), h(si["value"][:n_s]),
+                               0.01, 1.0 / N)
+        dt = time.perf_counter() - t0
+        cpu = {"value": n_s / dt, "unit": "trajectory-steps/s", "cores": 1, "kind": "oracle", "seconds": dt,
+               "sample": f"first {n_s} steps ({r_s} logit rows) of the batch, fp64 gradient"}
     print(json.dumps({
         "metric": "trajectory-steps/sec through the actor loss + logit gradient (eq. 1) + % peak HBM GB/s",
         "value": N * args.steps / elapsed, "unit": "trajectory-steps/s", "n_gpus": 1, "steps": args.steps,
@@ -69,7 +83,8 @@ def bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, ste
                    "logit_rows": R, "vocab": cfg.V, "grad_dtype": "bf16"},
         "roofline": {"bound": "hbm", "kernel": "k_actor_grad (+ k_actor_loss)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
+        "cpu_baseline": cpu}), flush=True)
 
 
 def _timed(torch, fn, steps, warmup):
@@ -105,6 +120,21 @@ def bench_retrace(args, b, torch, synth, dev):
         b.compute_priorities(td, rho, ent, off, cfg.w, step_prio=sp, traj_prio=tp)
     elapsed, ms = _timed(torch, step, args.steps, args.warmup)
     alg_bytes = N * (20 + 12) + N * (12 + 4) + cfg.B * 12     # retrace: 5 in + 3 out; priorities: 3 in + 1 out
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        h = lambda t: t.detach().cpu().numpy()
+        a = (h(lp), h(lm), h(si["reward"]), h(si["value"]), off_np, cfg.gamma, cfg.lam)
+        qh, eh = h(si["q"]), h(ent)
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 2.0:
+            o = oracle.retrace_targets(*a, q=qh)
+            oracle.compute_priorities(o["td"], o["rho"], eh, off_np, *cfg.w)
+            reps += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": N * reps / dt, "unit": "trajectory-steps/s", "cores": 1, "kind": "oracle", "seconds": dt,
+               "sample": f"the whole batch ({N} steps), {reps} repetitions"}
     print(json.dumps({
         "metric": "trajectory-steps/sec through Retrace + priorities (no logits) + % peak HBM GB/s",
         "value": N * args.steps / elapsed, "unit": "trajectory-steps/s", "n_gpus": 1, "steps": args.steps,
@@ -115,7 +145,8 @@ def bench_retrace(args, b, torch, synth, dev):
         "roofline": {"bound": "hbm", "kernel": "k_retrace + k_priorities (two launches; launch-latency bound)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
+        "cpu_baseline": cpu}), flush=True)
 
 
 def bench_replay(args, b, torch, synth, dev):
@@ -146,6 +177,20 @@ def bench_replay(args, b, torch, synth, dev):
     # per draw one 1 KB block of weights (the 4 KB of index entries it consults stay in cache) and
     # 16 B of I/O; per update 12 B in and one 64-byte sector read-modify-written
     alg_bytes = 2 * M * 4 + (M // 256) * 8 + K * (1024 + 8 + 8) + K * (8 + 4 + 64)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        h = lambda t: t.detach().cpu().numpy()
+        wh = h(w).copy()
+        t0 = time.perf_counter()
+        reps = 0
+        while reps < 3:
+            oi, _, _ = oracle.sample_prioritized(wh, h(uni[reps]))
+            oracle.update_priorities(wh, oi, h(prio[reps]), cfg.alpha)
+            reps += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": K * reps / dt, "unit": "draws/s", "cores": 1, "kind": "oracle", "seconds": dt,
+               "sample": f"{reps} iterations of sample + update on the full {M}-entry buffer"}
     print(json.dumps({
         "metric": "prioritized draws/sec incl. priority update and index rebuild + % peak HBM GB/s",
         "value": K * args.steps / elapsed, "unit": "draws/s", "n_gpus": 1, "steps": args.steps,
@@ -155,7 +200,8 @@ def bench_replay(args, b, torch, synth, dev):
         "roofline": {"bound": "hbm", "kernel": "k_sample + k_update_tag/commit + k_weight_max + k_super_sums + k_prefix_super",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms}}), flush=True)
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
+        "cpu_baseline": cpu}), flush=True)
 
 
 def main():
