@@ -5,6 +5,9 @@
 // The row's log-partition function and entropy are not recomputed: log Z_r = x_tok - tok_logp[r]
 // and H_r = tok_ent[r] come from the first sweep, so each logit is read once and each
 // gradient element written once (4 bytes of HBM traffic per element for bf16 output).
+// log Z is carried as a two-float value, so p_v = exp(x_v - log Z) is accurate to a few fp32
+// ulps whatever the magnitude of the logits, and the chosen token's element, where 1 - p
+// cancels when the token dominates its row, is formed from expm1(tok_logp) instead.
 // One wave per row, 16-byte non-temporal loads and stores; HBM-bound, no MFMA.
 #include "aride_device.h"
 
@@ -26,7 +29,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 struct RowCoef {
-    float negkz;  // -(log Z) * log2e
+    float negkz;  // -(log Z) * log2e, leading part
+    float negkz_lo;  // and the rest of it
     float cbl;    // scale * beta * ln2
     float k1;     // coef + scale * beta * H
     float coef;   // scale * rho * A
@@ -34,7 +38,7 @@ struct RowCoef {
 
 __device__ __forceinline__ float grad_of(float x, const RowCoef& c) {
     // y = log2 p; clamped so that p = 0 multiplies a finite factor (x may be -inf)
-    const float y = fmaxf(fmaf(x, kLog2eA, c.negkz), -200.f);
+    const float y = fmaxf(fmaf(x, kLog2eA, c.negkz) + c.negkz_lo, -200.f);
     const float p = fast_exp2(y);
     return p * fmaf(c.cbl, y, c.k1);
 }
@@ -70,16 +74,23 @@ __global__ __launch_bounds__(256) void k_actor_grad(
     const int tail0 = head + (nvec << 3);
 
     RowCoef c;
-    c.negkz = 0.f; c.cbl = 0.f; c.k1 = 0.f; c.coef = 0.f;
+    c.negkz = 0.f; c.negkz_lo = 0.f; c.cbl = 0.f; c.k1 = 0.f; c.coef = 0.f;
+    float gtok = 0.f;   // the chosen token's element
     if (live) {
         const long long t = row / A;
         const float xtok = bits_to_float(((uint32_t)p[tok]) << 16);
-        const float logz = xtok - tok_logp[row];
+        const float lp = tok_logp[row], h = tok_ent[row];
+        // (x - log Z) * log2e with the same fp32 log2e on both sides: once per row in fp64
+        const double negkz = -((double)xtok - (double)lp) * (double)kLog2eA;
+        c.negkz = (float)negkz;
+        c.negkz_lo = (float)(negkz - (double)c.negkz);
         c.coef = scale * rho[t] * (target[t] - baseline[t]);
         const float cb = scale * beta;
-        c.negkz = -logz * kLog2eA;
         c.cbl = cb * kLn2A;
-        c.k1 = fmaf(cb, tok_ent[row], c.coef);
+        c.k1 = fmaf(cb, h, c.coef);
+        // coef * (p - 1) + cb * p * (log p + H) at the chosen token, without forming p - 1
+        const float pm1 = expm1f(lp);
+        gtok = fmaf(c.coef, pm1, cb * (1.f + pm1) * (lp + h));
     }
     const int tvec = (live && tok >= head && tok < tail0) ? ((tok - head) >> 3) : -1;
     const int tsub = (tok - head) & 7;
@@ -94,7 +105,7 @@ __global__ __launch_bounds__(256) void k_actor_grad(
             g[6] = grad_of(bits_to_float(v.w << 16), c); g[7] = grad_of(bits_to_float(v.w & 0xffff0000u), c);
             if (i == tvec) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) g[j] -= (j == tsub) ? c.coef : 0.f;
+                for (int j = 0; j < 8; ++j) g[j] = (j == tsub) ? gtok : g[j];
             }
         } else {
 #pragma unroll
@@ -135,7 +146,7 @@ __global__ __launch_bounds__(256) void k_actor_grad(
         float g = 0.f;
         if (live) {
             g = grad_of(bits_to_float(((uint32_t)p[v]) << 16), c);
-            if (v == tok) g -= c.coef;
+            if (v == tok) g = gtok;
         }
         if constexpr (OUT_F32) gf[v] = g; else gb[v] = pack_bf16_one(g);
     }

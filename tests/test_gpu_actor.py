@@ -1,10 +1,12 @@
 """GPU parity: aride_actor_loss_grad (actor loss of eq. (1) and its logit gradient) against the
 CPU oracle.
 
-fp32 gradient: |g - o| <= 1e-4 * max(|o|, floor_r), floor_r = 1e-2 * scale * (|rho_t A_t| +
-beta * (1 + H_r)): elements a hundred times smaller than the row's gradient scale are held to
-an absolute bound (1e-6 of that scale, a few fp32 ulps), because p_v * (coef + beta*(log p_v + H))
-and the token's own entry -coef*(1 - p_tok) can cancel to exactly zero in the oracle.
+fp32 gradient: |g - o| <= 1e-4 * max(|o|, floor_r), floor_r = 3e-2 * scale * (|rho_t A_t| +
+beta * (1 + H_r)): elements well below the row's gradient scale are held to an absolute bound
+(3e-6 of that scale, some 25 fp32 ulps), because p_v * (coef + beta*(log p_v + H)) can cancel to
+exactly zero in the oracle, and because the token's own entry coef*(p_tok - 1) inherits, when the
+token dominates its row, the absolute error of tok_logp (a few fp32 ulps of 1: the row's
+partition sum is accumulated in fp32).
 bf16 gradient: bit-identical to the fp32 result rounded to nearest even, hence within one bf16
 ulp (2^-7 relative) of the oracle.
 """
@@ -40,7 +42,7 @@ def step_inputs(N, seed):
 
 def check_grad(got32, got16, want, rho, target, base, ent_rows, A, beta, scale, tag):
     coef = np.repeat(np.abs(npf(rho).astype(np.float64) * (npf(target).astype(np.float64) - npf(base))), A)
-    floor = 1e-2 * scale * (coef + beta * (1.0 + ent_rows))
+    floor = 3e-2 * scale * (coef + beta * (1.0 + ent_rows))
     err = np.abs(got32 - want)
     bound = 1e-4 * np.maximum(np.abs(want), floor[:, None])
     assert np.all(err <= bound), f"{tag}: fp32 gradient off; worst ratio {np.max(err / bound):.3f}"
@@ -134,7 +136,7 @@ def test_config1_full_size_sampled(oracle):
     o_score = oracle.score_logits(bits_of(logits[rt]), npf(tokens)[rows], 1, nthreads=8)
     got16 = npf(g16[rt].float()).astype(np.float64)
     coef = np.abs(npf(rho)[steps].astype(np.float64) * (npf(target)[steps].astype(np.float64) - npf(base)[steps]))
-    floor = 1e-2 * scale * (coef + beta * (1.0 + o_score["tok_ent"]))
+    floor = 3e-2 * scale * (coef + beta * (1.0 + o_score["tok_ent"]))
     bound = 2.0 ** -7 * np.abs(o_grad) + 1e-4 * floor[:, None] + 1e-38
     assert np.all(np.abs(got16 - o_grad) <= bound)
     # the loss needs only per-step quantities: check it against the oracle's formula on the device's sums
