@@ -204,6 +204,64 @@ def bench_replay(args, b, torch, synth, dev):
         "cpu_baseline": cpu}), flush=True)
 
 
+def bench_insert(args, b, torch, synth, dev):
+    """One step = K new entries appended to the circular 2^24-entry buffer (config 4 sizes) with the
+    sampling index brought up to date; --rebuild-every-insert forces the full rebuild for comparison."""
+    cfg = synth.CONFIGS[4]
+    seed = synth.BASE_SEED + cfg.index
+    M, K = cfg.M, cfg.K
+    w = torch.zeros(M, device=dev)
+    ws = b.Workspace(M, device=dev)
+    p0 = synth.replay_priorities(M, cfg.replay, seed + 5, dev)
+    for s0 in range(0, M, 1 << 22):
+        b.update_priorities(w, torch.arange(s0, min(M, s0 + (1 << 22)), device=dev), p0[s0:s0 + (1 << 22)], cfg.alpha, ws)
+    total = args.steps + args.warmup
+    prio = synth.td_errors(K * total, seed + 8, dev).abs().view(total, K)
+    it = [0]
+    cursor = [M - 3 * K - 17]          # the run wraps around the end of the buffer
+
+    def step():
+        i = it[0] % total
+        it[0] += 1
+        cursor[0] = b.replay_insert(w, cursor[0], prio[i], cfg.alpha, ws)
+        if args.rebuild_every_insert:
+            b.update_priorities(w, None, None, cfg.alpha, ws)
+    elapsed, ms = _timed(torch, step, args.steps, args.warmup)
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0, f"status flags {st.flags:#x} rc {rc}"
+    # per step: K priorities read, K weights written, the touched blocks read once more for their
+    # integer sums, their index entries rewritten (a rebuild instead sweeps all M weights twice)
+    alg_bytes = K * (4 + 4 + 4) + (K // 256 + 2) * (8 + 4)
+    if args.rebuild_every_insert:
+        alg_bytes += 2 * M * 4 + (M // 256) * 8
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        h = lambda t: t.detach().cpu().numpy()
+        wh = h(w).copy()
+        t0 = time.perf_counter()
+        reps, cur = 0, 0
+        while reps < 3:
+            cur, _ = oracle.replay_insert(wh, cur, h(prio[reps]), cfg.alpha)
+            oracle.quantise_weights(wh)          # the oracle's index is the whole prefix, rebuilt from scratch
+            reps += 1
+        dt = time.perf_counter() - t0
+        cpu = {"value": K * reps / dt, "unit": "entries/s", "cores": 1, "kind": "oracle", "seconds": dt,
+               "sample": f"{reps} inserts of {K} entries + quantisation of the full {M}-entry buffer"}
+    print(json.dumps({
+        "metric": "replay entries inserted/sec incl. keeping the sampling index current + % peak HBM GB/s",
+        "value": K * args.steps / elapsed, "unit": "entries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} (config {cfg.index}), circular insert", "replay_entries": M,
+                   "entries_per_insert": K, "alpha": cfg.alpha, "rebuild_every_insert": bool(args.rebuild_every_insert)},
+        "roofline": {"bound": "hbm", "kernel": "k_insert_patch + k_patch_supers + k_patch_finish (+ two gated no-ops)",
+                     "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
+        "cpu_baseline": cpu}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -212,11 +270,14 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = learner batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the CPU sample")
-    ap.add_argument("--path", choices=["scoring", "actor_grad", "retrace", "replay"], default="scoring",
+    ap.add_argument("--path", choices=["scoring", "actor_grad", "retrace", "replay", "insert"], default="scoring",
                     help="scoring: the five-call hot path on the learner batch (default). actor_grad: the actor "
                          "loss and its logit gradient (eq. (1)), the second sweep over the same logits. "
                          "retrace: retrace_targets + compute_priorities on the long-scan workload (config 3). "
-                         "replay: sample + update + index rebuild on the 2^24-entry buffer (config 4)")
+                         "replay: sample + update + index rebuild on the 2^24-entry buffer (config 4). "
+                         "insert: circular insert of 65 536 entries into that buffer, index patched")
+    ap.add_argument("--rebuild-every-insert", action="store_true",
+                    help="with --path insert: follow every insert by a full index rebuild (the comparison)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()
@@ -237,6 +298,8 @@ def main():
         return bench_retrace(args, b, torch, synth, dev)
     if args.path == "replay":
         return bench_replay(args, b, torch, synth, dev)
+    if args.path == "insert":
+        return bench_insert(args, b, torch, synth, dev)
     cfg = synth.CONFIGS[args.config]
     assert cfg.V > 0 and cfg.M > 0, "bench runs a workload with logits and a replay buffer"
     seed = synth.BASE_SEED + cfg.index

@@ -12,12 +12,11 @@ hipError_t retrace_launch(const float*, const float*, const float*, const float*
 hipError_t mc_returns_launch(const float*, const int*, int, int, float, float*, float*, hipStream_t);
 hipError_t priorities_launch(const float*, const float*, const float*, const int*, int, int, float,
                              float, float, float, float, float, int, float*, float*, hipStream_t);
-hipError_t update_launch(float*, long long, const long long*, const float*, int, float, WsHeader*,
-                         unsigned long long*, unsigned long long*, uint32_t*, hipStream_t);
-hipError_t insert_launch(float*, long long, long long, const float*, long long, float, long long*, WsHeader*,
-                         unsigned long long*, unsigned long long*, uint32_t*, hipStream_t);
-hipError_t sample_launch(const float*, long long, const WsHeader*, const unsigned long long*,
-                         const unsigned long long*, const double*, int, long long*, float*, uint32_t*,
+hipError_t update_launch(float*, long long, const long long*, const float*, int, float, const ReplayWs&,
+                         hipStream_t);
+hipError_t insert_launch(float*, long long, long long, const float*, long long, float, long long*,
+                         const ReplayWs&, hipStream_t);
+hipError_t sample_launch(const float*, long long, const ReplayWs&, const double*, int, long long*, float*,
                          hipStream_t);
 
 hipError_t actor_launch(const uint16_t*, long long, int, long long, const int*, int, const float*, const float*,
@@ -32,9 +31,7 @@ __global__ void k_fill_u64(unsigned long long* p, size_t n) {
         p[i] = 0ull;
 }
 
-static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-static inline size_t replay_blocks(int64_t M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
-static inline size_t index_bytes(int64_t M) { return M > 0 ? kSuperBytes + kPartBytes + round_up(replay_blocks(M) * 8, 256) : 0; }
+static inline size_t index_bytes(int64_t M) { return replay_index_bytes(M); }
 static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 }  // namespace aride
 
@@ -146,12 +143,8 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
     if (K >= (1 << 23) || !(alpha >= 0.f)) return ARIDE_E_RANGE;
     if (K > 0 && (!idx || !prio)) return ARIDE_E_NULL;
     if (K > 0 && misaligned(idx, 8)) return ARIDE_E_ALIGN;
-    WsHeader* hdr = (WsHeader*)ws;
-    unsigned long long* super_cum = (unsigned long long*)((char*)ws + kHeaderBytes);
-    uint32_t* partial_max = (uint32_t*)((char*)ws + kHeaderBytes + kSuperBytes);
-    unsigned long long* block_cum = (unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
-    hipError_t err = update_launch(weights, M, (const long long*)idx, prio, (int)K, alpha, hdr, block_cum,
-                                   super_cum, partial_max, (hipStream_t)stream);
+    hipError_t err = update_launch(weights, M, (const long long*)idx, prio, (int)K, alpha, replay_ws(ws, M),
+                                   (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
 
@@ -163,12 +156,8 @@ int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* 
     if (cursor < 0 || cursor >= M || !(alpha >= 0.f) || K > ((int64_t)1 << 40)) return ARIDE_E_RANGE;
     if (K > 0 && !prio) return ARIDE_E_NULL;
     if (slots_out && misaligned(slots_out, 8)) return ARIDE_E_ALIGN;
-    WsHeader* hdr = (WsHeader*)ws;
-    unsigned long long* super_cum = (unsigned long long*)((char*)ws + kHeaderBytes);
-    uint32_t* partial_max = (uint32_t*)((char*)ws + kHeaderBytes + kSuperBytes);
-    unsigned long long* block_cum = (unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
-    hipError_t err = insert_launch(weights, M, cursor, prio, K, alpha, (long long*)slots_out, hdr, block_cum,
-                                   super_cum, partial_max, (hipStream_t)stream);
+    hipError_t err = insert_launch(weights, M, cursor, prio, K, alpha, (long long*)slots_out, replay_ws(ws, M),
+                                   (hipStream_t)stream);
     if (err != hipSuccess) return ARIDE_E_HIP;
     if (cursor_out) *cursor_out = (cursor + K % M) % M;
     return ARIDE_OK;
@@ -184,12 +173,8 @@ int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t w
     if (K == 0) return ARIDE_OK;
     if (!uniforms || !idx_out) return ARIDE_E_NULL;
     if (misaligned(uniforms, 8) || misaligned(idx_out, 8)) return ARIDE_E_ALIGN;
-    const WsHeader* hdr = (const WsHeader*)ws;
-    const unsigned long long* super_cum = (const unsigned long long*)((char*)ws + kHeaderBytes);
-    const unsigned long long* block_cum =
-        (const unsigned long long*)((char*)ws + kHeaderBytes + kSuperBytes + kPartBytes);
-    hipError_t err = sample_launch(weights, M, hdr, block_cum, super_cum, uniforms, (int)K,
-                                   (long long*)idx_out, prob_out, (uint32_t*)ws, (hipStream_t)stream);
+    hipError_t err = sample_launch(weights, M, replay_ws(ws, M), uniforms, (int)K, (long long*)idx_out, prob_out,
+                                   (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
 }
 

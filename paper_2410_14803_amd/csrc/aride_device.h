@@ -13,6 +13,9 @@ constexpr int kWave = 64;
 //   [256, 256 + 2048)         super_cum: inclusive prefix of the super-block totals (256 x u64)
 //   [2304, 2304 + 4096)       partial_max: per-workgroup maxima of the last rebuild (1024 x u32)
 //   [6400, 6400 + 8*nblk)     block_cum: per super-block, inclusive prefix of its block sums
+//   then (256-byte aligned)   super_new: super-block totals handed from a patch pass to its last step (256 x u64)
+//   then                      chunk_max: bit pattern of the largest valid weight of each chunk of 16
+//                             blocks (4096 x u32); partial_max[g] covers the chunks 4g .. 4g+3
 struct WsHeader {
     uint32_t flags;      // OR of status bits
     uint32_t reserved;
@@ -21,11 +24,53 @@ struct WsHeader {
     int32_t exponent;    // e = ilogb(wmax) + 1
 };
 constexpr size_t kHeaderBytes = 256;
+
+// Private state of the replay index, at byte kIndexStateOffset of the header block.
+struct WsIndexState {
+    long long index_M;   // capacity for which chunk_max, partial_max and the prefixes are current (0: none)
+    uint32_t rebuild;    // set by a patch pass that found it cannot patch; read by the gated rebuild kernels
+};
+constexpr size_t kIndexStateOffset = 64;
 constexpr int kReplayBlock = 256;  // weights per indexed block: one wave reads one as 64 x float4
 constexpr int kSuperBlocks = 256;  // blocks per super-block (65536 weights); at most 256 super-blocks
 constexpr size_t kSuperBytes = kSuperBlocks * 8;
 constexpr int kMaxParts = 1024;    // workgroups of the maximum pass, one partial maximum each
 constexpr size_t kPartBytes = kMaxParts * 4;
+constexpr int kChunkBlocks = 16;   // blocks per chunk (4096 weights), the unit of the per-chunk maxima
+constexpr int kMaxChunks = 4096;   // chunks of the largest buffer
+constexpr size_t kChunkBytes = kMaxChunks * 4;
+
+// The arrays of the replay index inside a workspace sized for capacity M.
+struct ReplayWs {
+    WsHeader* hdr;
+    WsIndexState* ist;
+    unsigned long long* super_cum;
+    uint32_t* partial_max;
+    unsigned long long* block_cum;
+    unsigned long long* super_new;
+    uint32_t* chunk_max;
+};
+inline size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
+inline size_t replay_blocks(long long M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
+inline size_t replay_index_bytes(long long M) {
+    if (M <= 0) return 0;
+    const size_t nblk = replay_blocks(M);
+    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes;
+}
+inline ReplayWs replay_ws(void* ws, long long M) {
+    char* p = static_cast<char*>(ws);
+    const size_t nblk = replay_blocks(M);
+    ReplayWs w;
+    w.hdr = reinterpret_cast<WsHeader*>(p);
+    w.ist = reinterpret_cast<WsIndexState*>(p + kIndexStateOffset);
+    w.super_cum = reinterpret_cast<unsigned long long*>(p + kHeaderBytes);
+    w.partial_max = reinterpret_cast<uint32_t*>(p + kHeaderBytes + kSuperBytes);
+    w.block_cum = reinterpret_cast<unsigned long long*>(p + kHeaderBytes + kSuperBytes + kPartBytes);
+    char* after = p + kHeaderBytes + kSuperBytes + kPartBytes + round_up_256(nblk * 8);
+    w.super_new = reinterpret_cast<unsigned long long*>(after);
+    w.chunk_max = reinterpret_cast<uint32_t*>(after + kSuperBytes);
+    return w;
+}
 
 __device__ __forceinline__ float bits_to_float(uint32_t b) { return __uint_as_float(b); }
 __device__ __forceinline__ uint32_t float_to_bits(float f) { return __float_as_uint(f); }

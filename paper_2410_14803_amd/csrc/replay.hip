@@ -106,32 +106,89 @@ __global__ __launch_bounds__(256) void k_insert(float* __restrict__ weights, lon
     if (slots_out) slots_out[k] = slot;
 }
 
-// Pass A of the rebuild: largest valid weight (order-free, exact).  Each of the kMaxParts
-// workgroups writes the maximum of its share to partial_max; the consumers reduce those 1024
-// words themselves.  (One atomic per wave onto a single header word was measured at ~160 us
-// for M = 2^24: same-address atomics serialise.)
-__global__ __launch_bounds__(256) void k_weight_max(const float* __restrict__ weights, long long M, WsHeader* hdr,
-                                                    uint32_t* __restrict__ partial_max) {
-    __shared__ uint32_t wave_best[4];
-    const long long nvec = M >> 2;
-    const float4* wv = reinterpret_cast<const float4*>(weights);
+// Largest valid weight of the 256 weights of block `blk` (bit pattern; 0 when there is none),
+// reduced over the wave; `bad` collects negative, infinite or NaN entries (-0 is fine).
+__device__ __forceinline__ float4 load_block_quad(const float* __restrict__ weights, long long M, int blk, int lane) {
+    const long long base = (long long)blk * kReplayBlock + lane * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (base + 3 < M) v = *reinterpret_cast<const float4*>(weights + base);
+    else if (base < M) {
+        v.x = weights[base];
+        if (base + 1 < M) v.y = weights[base + 1];
+        if (base + 2 < M) v.z = weights[base + 2];
+    }
+    return v;
+}
+__device__ __forceinline__ uint32_t quad_max_bits(const float4& v, bool& bad) {
     uint32_t best = 0u;
-    bool bad = false;
     auto see = [&](float w) {
         const uint32_t b = float_to_bits(w);
         if (b < 0x7F800000u) best = max(best, b);          // non-negative finite: bit order = value order
-        else if (b != 0x80000000u) bad = true;              // negative, inf or NaN (-0 is fine)
+        else if (b != 0x80000000u) bad = true;
     };
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (long long)gridDim.x * blockDim.x) {
-        const float4 v = wv[i];
-        see(v.x); see(v.y); see(v.z); see(v.w);
-    }
-    if (blockIdx.x == 0 && threadIdx.x < (M & 3)) see(weights[(nvec << 2) + threadIdx.x]);
+    see(v.x); see(v.y); see(v.z); see(v.w);
+    return best;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) best = max(best, (uint32_t)__shfl_xor((int)best, d, kWave));
+    for (int d = 32; d >= 1; d >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, d, kWave));
+    return v;
+}
+
+// Pass A of the rebuild: largest valid weight (order-free, exact).  A chunk is 16 consecutive
+// blocks (4096 weights); wave w of workgroup g reduces chunk 4g + w -- 16 loads in flight,
+// one wave reduction -- and stores its maximum to chunk_max; the maximum of the workgroup's four
+// chunks goes to partial_max[g], and the consumers reduce those 1024 words themselves.  (One
+// atomic per wave onto a single header word was measured at ~160 us for M = 2^24: same-address
+// atomics serialise.)  With a gate, the kernel runs only when *gate is nonzero.
+static_assert(kMaxChunks == 4 * kMaxParts, "one chunk per wave of the maximum pass");
+static_assert((long long)kMaxChunks * kChunkBlocks * kReplayBlock >= (1 << 24), "chunks cover the largest buffer");
+
+__global__ __launch_bounds__(256) void k_weight_max(const float* __restrict__ weights, long long M, int nblk,
+                                                    WsHeader* hdr, uint32_t* __restrict__ partial_max,
+                                                    uint32_t* __restrict__ chunk_max,
+                                                    const uint32_t* __restrict__ gate) {
+    __shared__ uint32_t wave_best[4];
+    if (gate && *gate == 0u) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = 4 * blockIdx.x + wave;
+    const int first = chunk * kChunkBlocks;
+    uint32_t best = 0u;
+    bool bad = false;
+    if (first < nblk) {
+        const int count = min(kChunkBlocks, nblk - first);    // wave-uniform
+        float4 v[kChunkBlocks];
+        if (count == kChunkBlocks && (long long)(first + kChunkBlocks) * kReplayBlock <= M) {
+            const float4* src = reinterpret_cast<const float4*>(weights + (long long)first * kReplayBlock) + lane;
+#pragma unroll
+            for (int j = 0; j < kChunkBlocks; ++j) v[j] = src[j * kWave];
+        } else {                                               // the chunk that holds the end of the buffer
+#pragma unroll
+            for (int j = 0; j < kChunkBlocks; ++j) {
+                v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j < count) v[j] = load_block_quad(weights, M, first + j, lane);
+            }
+        }
+        // Non-negative finite floats order like their bit patterns and lie below 0x7F800000: when the
+        // plain unsigned maximum of this lane's bit patterns is below that, every entry was valid.
+        uint32_t raw = 0u;
+#pragma unroll
+        for (int j = 0; j < kChunkBlocks; ++j) {
+            raw = max(max(raw, float_to_bits(v[j].x)), float_to_bits(v[j].y));
+            raw = max(max(raw, float_to_bits(v[j].z)), float_to_bits(v[j].w));
+        }
+        if (raw < 0x7F800000u) {
+            best = raw;
+        } else {                                               // -0, negative, infinite or NaN among them
+#pragma unroll
+            for (int j = 0; j < kChunkBlocks; ++j) best = max(best, quad_max_bits(v[j], bad));
+        }
+    }
+    best = wave_max_u32(best);
     const bool any_bad = __any(bad);
-    if ((threadIdx.x & 63) == 0) {
-        wave_best[threadIdx.x >> 6] = best;
+    if (lane == 0) {
+        chunk_max[chunk] = best;
+        wave_best[wave] = best;
         if (any_bad) atomicOr(&hdr->flags, 0x2u);
     }
     __syncthreads();
@@ -174,32 +231,84 @@ __device__ __forceinline__ unsigned long long scan256(unsigned long long v, unsi
     return before + incl;
 }
 
-// Pass B: one workgroup of 1024 threads per super-block (65536 weights): each wave sums 16
-// blocks of 256 weights as integers, then the 256 block sums are scanned in LDS.  Writes the
-// within-super-block inclusive prefixes and the super-block's total.
-__global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ weights, long long M,
-                                                     const uint32_t* __restrict__ partial_max,
+// quantise for a guessed exponent: a weight above 2^e would leave the range the conversions
+// are defined on, so the scaled value is capped (such a sum is thrown away afterwards).
+__device__ __forceinline__ unsigned long long quantise_capped(float w, int e) {
+    const uint32_t b = float_to_bits(w);
+    const float wc = b < 0x7F800000u ? w : 0.f;
+    const float x = fminf(ldexpf(wc, 39 - e), 1099511627776.f);               // 2^40
+    const uint32_t hi = (uint32_t)(x * 2.3283064365386963e-10f);
+    const uint32_t lo = (uint32_t)fmaf(-(float)hi, 4294967296.f, x);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// The sweep of large buffers: one workgroup of 1024 threads per super-block (65536 weights);
+// each wave sums 16 blocks of 256 weights as integers, then the 256 block sums are scanned in
+// LDS.  Writes the within-super-block inclusive prefixes and the super-block's total.
+//
+// The exponent e = ilogb(max w) + 1 is only known once every weight has been seen, which
+// would make a rebuild two sweeps.  Between rebuilds it hardly ever changes, so:
+//   SPEC = true   one sweep that finds the maxima (chunk_max, partial_max, the bad-weight flag)
+//                 AND sums with the exponent of the index as it stands, a guess;
+//   SPEC = false  reduces partial_max to the true exponent and returns at once when the guess
+//                 was right (or the buffer has no mass: all sums are zero for any exponent);
+//                 otherwise it is the second sweep, with the true exponent.
+// With a gate, either runs only when *gate is nonzero.
+template <bool SPEC>
+__global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ weights, long long M, WsHeader* hdr,
+                                                     uint32_t* __restrict__ partial_max,
+                                                     uint32_t* __restrict__ chunk_max,
                                                      unsigned long long* __restrict__ block_cum, int nblk,
-                                                     unsigned long long* __restrict__ super_raw) {
+                                                     unsigned long long* __restrict__ super_raw,
+                                                     const uint32_t* __restrict__ gate) {
     __shared__ unsigned long long sums[kSuperBlocks];
     __shared__ unsigned long long wave_tot4[4];
     __shared__ uint32_t wave_best[16];
+    if (gate && *gate == 0u) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sblk = blockIdx.x;
-    const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
-    const int e = wb ? exponent_of(wb) : 0;
+    int e = 0;
+    if constexpr (!SPEC) {   // decided before any weight is read: this is usually all the kernel does
+        const uint32_t wb = reduce_partial_max<1024>(partial_max, wave_best);
+        if (wb == 0u) return;                          // the same for every thread of every workgroup
+        e = exponent_of(wb);
+        if (e == hdr->exponent) return;
+    }
     float4 v[16];
+    const int blk_first = sblk * kSuperBlocks + wave * 16;
+    if ((long long)(blk_first + 16) * kReplayBlock <= M) {     // wave-uniform: all 16 blocks inside the buffer
+        const float4* src = reinterpret_cast<const float4*>(weights + (long long)blk_first * kReplayBlock) + lane;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int blk = sblk * kSuperBlocks + wave * 16 + j;
-        const long long base = (long long)blk * kReplayBlock + lane * 4;
-        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (base + 3 < M) v[j] = *reinterpret_cast<const float4*>(weights + base);
-        else if (base < M) {
-            v[j].x = weights[base];
-            if (base + 1 < M) v[j].y = weights[base + 1];
-            if (base + 2 < M) v[j].z = weights[base + 2];
+        for (int j = 0; j < 16; ++j) v[j] = src[j * kWave];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = load_block_quad(weights, M, blk_first + j, lane);
+    }
+    if constexpr (SPEC) {
+        e = hdr->exponent;
+        // this wave's 16 blocks are chunk 16*sblk + wave (see k_weight_max for the two paths)
+        uint32_t raw = 0u, best = 0u;
+        bool bad = false;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            raw = max(max(raw, float_to_bits(v[j].x)), float_to_bits(v[j].y));
+            raw = max(max(raw, float_to_bits(v[j].z)), float_to_bits(v[j].w));
         }
+        if (raw < 0x7F800000u) {
+            best = raw;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) best = max(best, quad_max_bits(v[j], bad));
+        }
+        best = wave_max_u32(best);
+        const bool any_bad = __any(bad);
+        if (lane == 0) {
+            chunk_max[sblk * 16 + wave] = best;
+            wave_best[wave] = best;                    // read after the barrier below
+            if (any_bad) atomicOr(&hdr->flags, 0x2u);
+        }
+        // partial_max entries past the last super-block must not keep an older, larger buffer's maxima
+        if (sblk == 0) for (int i = 4 * (int)gridDim.x + tid; i < kMaxParts; i += 1024) partial_max[i] = 0u;
     }
     // Four wave-wide sums at a time, so that a wave starts reducing as soon as its first four
     // loads are back while the rest are still in flight.  In each of two exchange rounds a lane
@@ -212,7 +321,11 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float4 w = v[4 * g + j];
-            part[j] = wb != 0u ? quantise(w.x, e) + quantise(w.y, e) + quantise(w.z, e) + quantise(w.w, e) : 0ull;
+            if constexpr (SPEC)
+                part[j] = quantise_capped(w.x, e) + quantise_capped(w.y, e) + quantise_capped(w.z, e) +
+                          quantise_capped(w.w, e);
+            else
+                part[j] = quantise(w.x, e) + quantise(w.y, e) + quantise(w.z, e) + quantise(w.w, e);
         }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -230,6 +343,11 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
         if ((lane & 15) == 0) sums[wave * 16 + 4 * g + (lane >> 4)] = part[0];
     }
     __syncthreads();
+    if constexpr (SPEC) {
+        if (tid < 4)
+            partial_max[4 * sblk + tid] = max(max(wave_best[4 * tid], wave_best[4 * tid + 1]),
+                                              max(wave_best[4 * tid + 2], wave_best[4 * tid + 3]));
+    }
     unsigned long long total = 0ull;
     const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
     if (tid < kSuperBlocks) {
@@ -268,7 +386,8 @@ __global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ we
 // With a single super-block (gridDim.x == 1) it also does the work of k_prefix_super.
 __global__ __launch_bounds__(256) void k_scan_supers(unsigned long long* __restrict__ block_cum, int nblk,
                                                      unsigned long long* __restrict__ super_raw,
-                                                     const uint32_t* __restrict__ partial_max, WsHeader* hdr) {
+                                                     const uint32_t* __restrict__ partial_max, WsHeader* hdr,
+                                                     WsIndexState* ist, long long M) {
     __shared__ unsigned long long wave_tot4[4];
     __shared__ uint32_t wave_best[4];
     const int blk = blockIdx.x * kSuperBlocks + threadIdx.x;
@@ -286,13 +405,16 @@ __global__ __launch_bounds__(256) void k_scan_supers(unsigned long long* __restr
         hdr->total = total;
         hdr->exponent = wb ? exponent_of(wb) : 0;
         if (total == 0ull) atomicOr(&hdr->flags, 0x4u);
+        ist->index_M = M;
+        ist->rebuild = 0u;
     }
 }
 
 // Pass C: inclusive prefix of the (at most 256) super-block totals, padded with Total; also
 // publishes Total, the exponent and the no-mass flag.
 __global__ __launch_bounds__(256) void k_prefix_super(unsigned long long* __restrict__ super_cum, int nsuper,
-                                                      const uint32_t* __restrict__ partial_max, WsHeader* hdr) {
+                                                      const uint32_t* __restrict__ partial_max, WsHeader* hdr,
+                                                      WsIndexState* ist, long long M) {
     __shared__ unsigned long long wave_tot4[4];
     __shared__ uint32_t wave_best[4];
     const int tid = threadIdx.x;
@@ -305,6 +427,176 @@ __global__ __launch_bounds__(256) void k_prefix_super(unsigned long long* __rest
         hdr->total = total;
         hdr->exponent = wb ? exponent_of(wb) : 0;
         if (total == 0ull) atomicOr(&hdr->flags, 0x4u);
+        ist->index_M = M;     // chunk_max, partial_max and the prefixes describe these M weights
+        ist->rebuild = 0u;
+    }
+}
+
+// ---- Patching the index after a contiguous insert (Appendix A.4.2, circular buffer) ----------
+// Inserting K entries at the cursor changes the blocks b0, b0+1, ... (nt of them, circularly);
+// everything else in the index stays valid as long as the exponent e = ilogb(max w) + 1 does.
+//   1. k_insert_patch   one workgroup per touched chunk of 16 blocks, one wave per block: store
+//                       the new weights, refresh chunk_max
+//   2. k_patch_supers   one workgroup per touched super-block: new maximum of the buffer from
+//                       partial_max / chunk_max; same exponent -> recompute the touched blocks'
+//                       integer sums, rescan the super-block; otherwise raise the rebuild gate
+//   3. k_super_sums<true>, <false> with the gate: the ordinary rebuild, which runs only then
+//   4. k_patch_finish   prefix over the super-block totals, header
+// No step waits for the host, so the choice between patch and rebuild is taken on the device.
+
+// A block is touched when its circular distance from b0 is below nt.
+__device__ __forceinline__ bool in_circular(int x, int start, int count, int modulus) {
+    int d = x - start;
+    if (d < 0) d += modulus;
+    return d < count;
+}
+
+__global__ __launch_bounds__(1024) void k_insert_patch(float* __restrict__ weights, long long M, int nblk, int nchunk,
+                                                       long long cursor, const float* __restrict__ prio, long long K,
+                                                       float alpha, long long* __restrict__ slots_out, int c0,
+                                                       WsHeader* hdr, uint32_t* __restrict__ chunk_max) {
+    __shared__ uint32_t wave_best[kChunkBlocks];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int chunk = c0 + blockIdx.x;                 // the touched chunks c0, c0+1, ... (circular)
+    if (chunk >= nchunk) chunk -= nchunk;
+    const int blk = chunk * kChunkBlocks + wave;
+    uint32_t best = 0u;
+    bool bad = false;
+    if (blk < nblk) {                            // wave-uniform
+        const long long base = (long long)blk * kReplayBlock + lane * 4;
+        float w[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const long long i = base + c;
+            if (i >= M) continue;
+            long long k = i - cursor;
+            if (k < 0) k += M;
+            if (k < K) {                         // K <= M here: every slot receives at most one entry
+                double p = (double)prio[k];
+                if (!(p > 0.0)) p = 0.0;
+                w[c] = (float)pow(p, (double)alpha);
+                weights[i] = w[c];
+                if (slots_out) slots_out[k] = i;
+            } else {
+                w[c] = weights[i];
+            }
+        }
+        best = wave_max_u32(quad_max_bits(make_float4(w[0], w[1], w[2], w[3]), bad));
+    }
+    const bool any_bad = __any(bad);
+    if (lane == 0) {
+        wave_best[wave] = best;
+        if (any_bad) atomicOr(&hdr->flags, 0x2u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t cb = 0u;
+#pragma unroll
+        for (int j = 0; j < kChunkBlocks; ++j) cb = max(cb, wave_best[j]);
+        chunk_max[chunk] = cb;
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_patch_supers(const float* __restrict__ weights, long long M, int nblk,
+                                                       int b0, int nt, int c0, int nc, int nchunk, int s0, int nsuper,
+                                                       const WsHeader* __restrict__ hdr, WsIndexState* ist,
+                                                       uint32_t* __restrict__ partial_max,
+                                                       const uint32_t* __restrict__ chunk_max,
+                                                       unsigned long long* __restrict__ block_cum,
+                                                       unsigned long long* __restrict__ super_new) {
+    __shared__ unsigned long long sums[kSuperBlocks];
+    __shared__ unsigned long long wave_tot4[4];
+    __shared__ uint32_t wave_best[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int s = s0 + blockIdx.x;
+    if (s >= nsuper) s -= nsuper;
+
+    // New maximum of the whole buffer: thread g answers for the four chunks 4g .. 4g+3 that
+    // partial_max[g] covers.  If one of them was touched the four are reduced again from
+    // chunk_max (and workgroup 0 stores the result); the others still have their maximum in
+    // partial_max, which nobody writes here.
+    uint32_t best = 0u;
+    {
+        const int first = 4 * tid, last = min(first + 4, nchunk);
+        if (first < last) {
+            const bool touched = in_circular(first, c0, nc, nchunk) || (c0 >= first && c0 < last);
+            if (touched) {
+                for (int c = first; c < last; ++c) best = max(best, chunk_max[c]);
+                if (blockIdx.x == 0) partial_max[tid] = best;
+            } else {
+                best = partial_max[tid];
+            }
+        }
+    }
+    best = wave_max_u32(best);
+    if (lane == 0) wave_best[wave] = best;
+    __syncthreads();
+    uint32_t wb = 0u;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) wb = max(wb, wave_best[w]);
+
+    const int e = hdr->exponent;
+    const bool rebuild = ist->index_M != M || wb == 0u || exponent_of(wb) != e;
+    if (rebuild) {           // the same for every thread of every workgroup
+        if (blockIdx.x == 0 && tid == 0) ist->rebuild = 1u;
+        return;
+    }
+
+    // Block sums of this super-block: the old ones from the differences of the old prefix, the
+    // touched ones recomputed from the weights.
+    const int blk0 = s * kSuperBlocks;
+    if (tid < kSuperBlocks) {
+        const int blk = blk0 + tid;
+        unsigned long long v = 0ull;
+        if (blk < nblk) v = block_cum[blk] - (tid > 0 ? block_cum[blk - 1] : 0ull);
+        sums[tid] = v;
+    }
+    __syncthreads();
+    for (int j = 0; j < 16; ++j) {
+        const int blk = blk0 + wave * 16 + j;
+        if (blk >= nblk || !in_circular(blk, b0, nt, nblk)) continue;    // wave-uniform
+        const float4 v = load_block_quad(weights, M, blk, lane);
+        unsigned long long q = quantise(v.x, e) + quantise(v.y, e) + quantise(v.z, e) + quantise(v.w, e);
+        q = wave_sum_u64(q);
+        if (lane == 0) sums[wave * 16 + j] = q;
+    }
+    __syncthreads();
+    unsigned long long total = 0ull;
+    const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
+    if (tid < kSuperBlocks) {
+        const int blk = blk0 + tid;
+        if (blk < nblk) block_cum[blk] = incl;
+        if (tid == 0) super_new[s] = total;
+    }
+}
+
+// Last step of a patch: raw super-block totals are the new ones (super_new) for the touched
+// super-blocks -- for all of them after a gated rebuild -- and the differences of the old
+// prefix for the rest; then as k_prefix_super.
+__global__ __launch_bounds__(256) void k_patch_finish(unsigned long long* __restrict__ super_cum,
+                                                      const unsigned long long* __restrict__ super_new, int nsuper,
+                                                      int s0, int ns, const uint32_t* __restrict__ partial_max,
+                                                      WsHeader* hdr, WsIndexState* ist, long long M) {
+    __shared__ unsigned long long wave_tot4[4];
+    __shared__ uint32_t wave_best[4];
+    const int tid = threadIdx.x;
+    const bool rebuilt = ist->rebuild != 0u;
+    const uint32_t wb = reduce_partial_max<256>(partial_max, wave_best);   // barrier: every thread has read the gate
+    unsigned long long raw = 0ull;
+    if (tid < nsuper) {
+        if (rebuilt || in_circular(tid, s0, ns, nsuper)) raw = super_new[tid];
+        else raw = super_cum[tid] - (tid > 0 ? super_cum[tid - 1] : 0ull);
+    }
+    unsigned long long total = 0ull;
+    const unsigned long long incl = scan256(raw, wave_tot4, total);        // barrier before the stores below
+    super_cum[tid] = incl;    // entries past nsuper repeat Total
+    if (tid == 0) {
+        hdr->wmax_bits = wb;
+        hdr->total = total;
+        hdr->exponent = wb ? exponent_of(wb) : 0;
+        if (total == 0ull) atomicOr(&hdr->flags, 0x4u);
+        ist->index_M = M;
+        ist->rebuild = 0u;
     }
 }
 
@@ -318,7 +610,7 @@ constexpr int kFusedSuperMin = 64;      // from this many super-blocks on, one w
 
 __global__ __launch_bounds__(1024) void k_update_small(
     float* __restrict__ weights, int M, const long long* __restrict__ idx, const float* __restrict__ prio,
-    int K, float alpha, WsHeader* hdr, unsigned long long* __restrict__ block_cum, int nblk,
+    int K, float alpha, WsHeader* hdr, WsIndexState* ist, unsigned long long* __restrict__ block_cum, int nblk,
     unsigned long long* __restrict__ super_cum) {
     __shared__ unsigned long long sums[1024];
     __shared__ unsigned long long wave_tot[16];
@@ -397,6 +689,8 @@ __global__ __launch_bounds__(1024) void k_update_small(
         hdr->exponent = e;
         uint32_t f = (any_bad ? 0x2u : 0u) | (total == 0ull ? 0x4u : 0u);
         if (f) atomicOr(&hdr->flags, f);
+        ist->index_M = 0;     // this path keeps no per-block maxima
+        ist->rebuild = 0u;
     }
 }
 
@@ -509,55 +803,82 @@ __global__ __launch_bounds__(256) void k_sample(
 }
 
 hipError_t update_launch(float* weights, long long M, const long long* idx, const float* prio, int K,
-                         float alpha, WsHeader* hdr, unsigned long long* block_cum,
-                         unsigned long long* super_cum, uint32_t* partial_max, hipStream_t st) {
+                         float alpha, const ReplayWs& w, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
     const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
     if (M <= kSmallReplay && K <= kSmallBatch) {
         hipLaunchKernelGGL(k_update_small, dim3(1), dim3(1024), 0, st, weights, (int)M, idx, prio, K, alpha,
-                           hdr, block_cum, nblk, super_cum);
+                           w.hdr, w.ist, w.block_cum, nblk, w.super_cum);
         return hipGetLastError();
     }
     if (K > 0 && K <= kSmallBatch) {
-        hipLaunchKernelGGL(k_update_scatter_small, dim3(1), dim3(1024), 0, st, weights, M, idx, prio, K, alpha, hdr);
+        hipLaunchKernelGGL(k_update_scatter_small, dim3(1), dim3(1024), 0, st, weights, M, idx, prio, K, alpha, w.hdr);
     } else if (K > 0) {
         const unsigned g = (unsigned)((K + 255) / 256);
-        hipLaunchKernelGGL(k_update_tag, dim3(g), dim3(256), 0, st, weights, M, idx, K, hdr);
+        hipLaunchKernelGGL(k_update_tag, dim3(g), dim3(256), 0, st, weights, M, idx, K, w.hdr);
         hipLaunchKernelGGL(k_update_commit, dim3(g), dim3(256), 0, st, weights, M, idx, prio, K, alpha);
     }
-    hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, hdr, partial_max);
     if (nsuper >= kFusedSuperMin) {
-        hipLaunchKernelGGL(k_super_sums, dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, partial_max,
-                           block_cum, nblk, super_cum);
+        const uint32_t* always = nullptr;
+        hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, always);
+        hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, always);
     } else {
+        hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, nblk, w.hdr, w.partial_max,
+                           w.chunk_max, (const uint32_t*)nullptr);
         hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M,
-                           partial_max, block_cum, nblk);
-        hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, block_cum, nblk, super_cum,
-                           partial_max, hdr);
+                           w.partial_max, w.block_cum, nblk);
+        hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, w.block_cum, nblk, w.super_cum,
+                           w.partial_max, w.hdr, w.ist, M);
         if (nsuper == 1) return hipGetLastError();   // the scan kernel finalised the index itself
     }
-    hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, super_cum, nsuper, partial_max, hdr);
+    hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, w.super_cum, nsuper, w.partial_max, w.hdr, w.ist, M);
     return hipGetLastError();
 }
 
+// Large buffers and short batches are patched; everything else is inserted and rebuilt.
+constexpr int kPatchFraction = 8;   // patch when K <= M / kPatchFraction
+
 hipError_t insert_launch(float* weights, long long M, long long cursor, const float* prio, long long K,
-                         float alpha, long long* slots_out, WsHeader* hdr, unsigned long long* block_cum,
-                         unsigned long long* super_cum, uint32_t* partial_max, hipStream_t st) {
+                         float alpha, long long* slots_out, const ReplayWs& w, hipStream_t st) {
+    const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
+    const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
+    if (K > 0 && nsuper >= kFusedSuperMin && K <= M / kPatchFraction) {
+        const int nchunk = (nblk + kChunkBlocks - 1) / kChunkBlocks;
+        const int b0 = (int)(cursor / kReplayBlock);
+        const int b1 = (int)(((cursor + K - 1) % M) / kReplayBlock);
+        const int nt = (b1 - b0 + nblk) % nblk + 1;              // touched blocks b0, b0+1, ... (circular)
+        const int c0 = b0 / kChunkBlocks, c1 = b1 / kChunkBlocks;
+        const int nc = (c1 - c0 + nchunk) % nchunk + 1;          // touched chunks c0, c0+1, ...
+        const int s0 = b0 / kSuperBlocks, s1 = b1 / kSuperBlocks;
+        const int ns = (s1 - s0 + nsuper) % nsuper + 1;          // touched super-blocks s0, s0+1, ...
+        const uint32_t* gate = &w.ist->rebuild;
+        hipLaunchKernelGGL(k_insert_patch, dim3((unsigned)nc), dim3(1024), 0, st, weights, M, nblk, nchunk, cursor,
+                           prio, K, alpha, slots_out, c0, w.hdr, w.chunk_max);
+        hipLaunchKernelGGL(k_patch_supers, dim3((unsigned)ns), dim3(1024), 0, st, weights, M, nblk, b0, nt, c0, nc,
+                           nchunk, s0, nsuper, w.hdr, w.ist, w.partial_max, w.chunk_max, w.block_cum, w.super_new);
+        hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, gate);
+        hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, gate);
+        hipLaunchKernelGGL(k_patch_finish, dim3(1), dim3(256), 0, st, w.super_cum, w.super_new, nsuper, s0, ns,
+                           w.partial_max, w.hdr, w.ist, M);
+        return hipGetLastError();
+    }
     if (K > 0)
         hipLaunchKernelGGL(k_insert, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, weights, M, cursor, prio,
                            K, alpha, slots_out);
-    return update_launch(weights, M, nullptr, nullptr, 0, alpha, hdr, block_cum, super_cum, partial_max, st);
+    return update_launch(weights, M, nullptr, nullptr, 0, alpha, w, st);
 }
 
-hipError_t sample_launch(const float* weights, long long M, const WsHeader* hdr,
-                         const unsigned long long* block_cum, const unsigned long long* super_cum,
-                         const double* uniforms, int K, long long* idx_out, float* prob_out,
-                         uint32_t* flags, hipStream_t st) {
+hipError_t sample_launch(const float* weights, long long M, const ReplayWs& w, const double* uniforms, int K,
+                         long long* idx_out, float* prob_out, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
     const long long waves = ((long long)K + 3) / 4;      // four draws per wave
     const unsigned g = (unsigned)((waves * kWave + 255) / 256);
-    hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, hdr, block_cum, nblk, super_cum,
-                       uniforms, K, idx_out, prob_out, flags);
+    hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, w.hdr, w.block_cum, nblk, w.super_cum,
+                       uniforms, K, idx_out, prob_out, &w.hdr->flags);
     return hipGetLastError();
 }
 

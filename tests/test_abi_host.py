@@ -38,7 +38,8 @@ def test_error_codes_match_header():
 
 def test_workspace_bytes(L):
     assert b.workspace_bytes(0) == 256                       # status block only
-    fixed = 256 + 2048 + 4096                                # status, super-block prefixes, partial maxima
+    # status, super-block prefixes, partial maxima, new super-block totals, per-chunk maxima
+    fixed = 256 + 2048 + 4096 + 2048 + 16384
     assert b.workspace_bytes(1) == fixed + 256               # one block prefix, rounded to 256
     assert b.workspace_bytes(256 * 32) == fixed + 256
     assert b.workspace_bytes(256 * 32 + 1) == fixed + 512
