@@ -16,6 +16,9 @@ constexpr int kWave = 64;
 //   then (256-byte aligned)   super_new: super-block totals handed from a patch pass to its last step (256 x u64)
 //   then                      chunk_max: bit pattern of the largest valid weight of each chunk of 16
 //                             blocks (4096 x u32); partial_max[g] covers the chunks 4g .. 4g+3
+//   then                      quarter_max: maxima of the quarter chunks (4 blocks) an insert has just
+//                             touched, handed from its first step to its second (16384 x u32)
+//   then                      touched_sum: integer sums of the blocks of those chunks, by position (8448 x u64)
 struct WsHeader {
     uint32_t flags;      // OR of status bits
     uint32_t reserved;
@@ -39,6 +42,9 @@ constexpr size_t kPartBytes = kMaxParts * 4;
 constexpr int kChunkBlocks = 16;   // blocks per chunk (4096 weights), the unit of the per-chunk maxima
 constexpr int kMaxChunks = 4096;   // chunks of the largest buffer
 constexpr size_t kChunkBytes = kMaxChunks * 4;
+constexpr size_t kQuarterBytes = 4 * kChunkBytes;
+constexpr int kMaxTouched = 8448;  // blocks of the chunks one patched insert may touch
+constexpr size_t kTouchedBytes = kMaxTouched * 8;
 
 // The arrays of the replay index inside a workspace sized for capacity M.
 struct ReplayWs {
@@ -49,13 +55,15 @@ struct ReplayWs {
     unsigned long long* block_cum;
     unsigned long long* super_new;
     uint32_t* chunk_max;
+    uint32_t* quarter_max;
+    unsigned long long* touched_sum;
 };
 inline size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
 inline size_t replay_blocks(long long M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
 inline size_t replay_index_bytes(long long M) {
     if (M <= 0) return 0;
     const size_t nblk = replay_blocks(M);
-    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes;
+    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes;
 }
 inline ReplayWs replay_ws(void* ws, long long M) {
     char* p = static_cast<char*>(ws);
@@ -69,6 +77,8 @@ inline ReplayWs replay_ws(void* ws, long long M) {
     char* after = p + kHeaderBytes + kSuperBytes + kPartBytes + round_up_256(nblk * 8);
     w.super_new = reinterpret_cast<unsigned long long*>(after);
     w.chunk_max = reinterpret_cast<uint32_t*>(after + kSuperBytes);
+    w.quarter_max = reinterpret_cast<uint32_t*>(after + kSuperBytes + kChunkBytes);
+    w.touched_sum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes);
     return w;
 }
 

@@ -231,6 +231,27 @@ __device__ __forceinline__ unsigned long long scan256(unsigned long long v, unsi
     return before + incl;
 }
 
+// Four wave-wide sums at once: in each of two exchange rounds a lane hands half of its partial
+// sums to the partner lane and keeps the other half (the number of live values halves, the
+// number of lanes sharing each doubles); four more rounds finish the one value left.
+// Returns, in lane L, the wave-wide sum of part[L >> 4] (7 shuffles instead of 24).
+__device__ __forceinline__ unsigned long long transposed_sum4(unsigned long long (&part)[4], int lane) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int half = 2 >> s, mask = 32 >> s;
+        const bool upper = (lane & mask) != 0;
+#pragma unroll
+        for (int i = 0; i < half; ++i) {
+            const unsigned long long keep = upper ? part[i + half] : part[i];
+            const unsigned long long send = upper ? part[i] : part[i + half];
+            part[i] = keep + __shfl_xor(send, mask, kWave);
+        }
+    }
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) part[0] += __shfl_xor(part[0], d, kWave);
+    return part[0];
+}
+
 // quantise for a guessed exponent: a weight above 2^e would leave the range the conversions
 // are defined on, so the scaled value is capped (such a sum is thrown away afterwards).
 __device__ __forceinline__ unsigned long long quantise_capped(float w, int e) {
@@ -310,11 +331,8 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
         // partial_max entries past the last super-block must not keep an older, larger buffer's maxima
         if (sblk == 0) for (int i = 4 * (int)gridDim.x + tid; i < kMaxParts; i += 1024) partial_max[i] = 0u;
     }
-    // Four wave-wide sums at a time, so that a wave starts reducing as soon as its first four
-    // loads are back while the rest are still in flight.  In each of two exchange rounds a lane
-    // hands half of its partial sums to the partner lane and keeps the other half (the number
-    // of live values halves, the number of lanes sharing each doubles); four more rounds finish
-    // the one value left.  Afterwards lane L holds the sum of block 4g + (L >> 4).
+    // Four blocks at a time, so that a wave starts reducing as soon as its first four loads are
+    // back while the rest are still in flight; lane L ends up with the sum of block 4g + (L >> 4).
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         unsigned long long part[4];
@@ -327,20 +345,8 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
             else
                 part[j] = quantise(w.x, e) + quantise(w.y, e) + quantise(w.z, e) + quantise(w.w, e);
         }
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int half = 2 >> s, mask = 32 >> s;
-            const bool upper = (lane & mask) != 0;
-#pragma unroll
-            for (int i = 0; i < half; ++i) {
-                const unsigned long long keep = upper ? part[i + half] : part[i];
-                const unsigned long long send = upper ? part[i] : part[i + half];
-                part[i] = keep + __shfl_xor(send, mask, kWave);
-            }
-        }
-#pragma unroll
-        for (int d = 8; d >= 1; d >>= 1) part[0] += __shfl_xor(part[0], d, kWave);
-        if ((lane & 15) == 0) sums[wave * 16 + 4 * g + (lane >> 4)] = part[0];
+        const unsigned long long sum = transposed_sum4(part, lane);
+        if ((lane & 15) == 0) sums[wave * 16 + 4 * g + (lane >> 4)] = sum;
     }
     __syncthreads();
     if constexpr (SPEC) {
@@ -435,11 +441,12 @@ __global__ __launch_bounds__(256) void k_prefix_super(unsigned long long* __rest
 // ---- Patching the index after a contiguous insert (Appendix A.4.2, circular buffer) ----------
 // Inserting K entries at the cursor changes the blocks b0, b0+1, ... (nt of them, circularly);
 // everything else in the index stays valid as long as the exponent e = ilogb(max w) + 1 does.
-//   1. k_insert_patch   one workgroup per touched chunk of 16 blocks, one wave per block: store
-//                       the new weights, refresh chunk_max
+//   1. k_insert_patch   four workgroups per touched chunk of 16 blocks, one wave per block: store
+//                       the new weights, leave the maximum of each quarter chunk in quarter_max
+//                       and each block's integer sum under the standing exponent in touched_sum
 //   2. k_patch_supers   one workgroup per touched super-block: new maximum of the buffer from
-//                       partial_max / chunk_max; same exponent -> recompute the touched blocks'
-//                       integer sums, rescan the super-block; otherwise raise the rebuild gate
+//                       partial_max / chunk_max / quarter_max; same exponent -> put the touched
+//                       blocks' new sums in, rescan the super-block; otherwise raise the rebuild gate
 //   3. k_super_sums<true>, <false> with the gate: the ordinary rebuild, which runs only then
 //   4. k_patch_finish   prefix over the super-block totals, header
 // No step waits for the host, so the choice between patch and rebuild is taken on the device.
@@ -451,15 +458,17 @@ __device__ __forceinline__ bool in_circular(int x, int start, int count, int mod
     return d < count;
 }
 
-__global__ __launch_bounds__(1024) void k_insert_patch(float* __restrict__ weights, long long M, int nblk, int nchunk,
-                                                       long long cursor, const float* __restrict__ prio, long long K,
-                                                       float alpha, long long* __restrict__ slots_out, int c0,
-                                                       WsHeader* hdr, uint32_t* __restrict__ chunk_max) {
-    __shared__ uint32_t wave_best[kChunkBlocks];
+__global__ __launch_bounds__(256) void k_insert_patch(float* __restrict__ weights, long long M, int nblk, int nchunk,
+                                                      long long cursor, const float* __restrict__ prio, long long K,
+                                                      float alpha, long long* __restrict__ slots_out, int c0,
+                                                      WsHeader* hdr, uint32_t* __restrict__ quarter_max,
+                                                      unsigned long long* __restrict__ touched_sum) {
+    __shared__ uint32_t wave_best[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int chunk = c0 + blockIdx.x;                 // the touched chunks c0, c0+1, ... (circular)
+    int chunk = c0 + (int)(blockIdx.x >> 2);     // the touched chunks c0, c0+1, ... (circular)
     if (chunk >= nchunk) chunk -= nchunk;
-    const int blk = chunk * kChunkBlocks + wave;
+    const int quarter = 4 * chunk + (int)(blockIdx.x & 3);
+    const int blk = 4 * quarter + wave;
     uint32_t best = 0u;
     bool bad = false;
     if (blk < nblk) {                            // wave-uniform
@@ -482,6 +491,11 @@ __global__ __launch_bounds__(1024) void k_insert_patch(float* __restrict__ weigh
             }
         }
         best = wave_max_u32(quad_max_bits(make_float4(w[0], w[1], w[2], w[3]), bad));
+        // the block's integer sum under the standing exponent, a guess that k_patch_supers checks
+        const int e = hdr->exponent;
+        const unsigned long long q = wave_sum_u64(quantise_capped(w[0], e) + quantise_capped(w[1], e) +
+                                                  quantise_capped(w[2], e) + quantise_capped(w[3], e));
+        if (lane == 0) touched_sum[4 * blockIdx.x + wave] = q;    // by position: block 16*c0 is entry 0
     }
     const bool any_bad = __any(bad);
     if (lane == 0) {
@@ -489,39 +503,64 @@ __global__ __launch_bounds__(1024) void k_insert_patch(float* __restrict__ weigh
         if (any_bad) atomicOr(&hdr->flags, 0x2u);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t cb = 0u;
-#pragma unroll
-        for (int j = 0; j < kChunkBlocks; ++j) cb = max(cb, wave_best[j]);
-        chunk_max[chunk] = cb;
-    }
+    if (threadIdx.x == 0)
+        quarter_max[quarter] = max(max(wave_best[0], wave_best[1]), max(wave_best[2], wave_best[3]));
 }
 
-__global__ __launch_bounds__(1024) void k_patch_supers(const float* __restrict__ weights, long long M, int nblk,
-                                                       int b0, int nt, int c0, int nc, int nchunk, int s0, int nsuper,
+__global__ __launch_bounds__(1024) void k_patch_supers(long long M, int nblk, int b0, int nt, int c0, int nc,
+                                                       int nchunk, int s0, int nsuper,
                                                        const WsHeader* __restrict__ hdr, WsIndexState* ist,
                                                        uint32_t* __restrict__ partial_max,
-                                                       const uint32_t* __restrict__ chunk_max,
+                                                       uint32_t* __restrict__ chunk_max,
+                                                       const uint32_t* __restrict__ quarter_max,
+                                                       const unsigned long long* __restrict__ touched_sum,
                                                        unsigned long long* __restrict__ block_cum,
                                                        unsigned long long* __restrict__ super_new) {
-    __shared__ unsigned long long sums[kSuperBlocks];
     __shared__ unsigned long long wave_tot4[4];
     __shared__ uint32_t wave_best[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int s = s0 + blockIdx.x;
     if (s >= nsuper) s -= nsuper;
+    const int blk0 = s * kSuperBlocks;
+
+    // Everything the kernel reads is asked for up front: the standing exponent, the capacity the
+    // index was built for, and this super-block's block sums -- a touched block's from
+    // k_insert_patch, the others' from the differences of the old prefix.
+    const int e = hdr->exponent;
+    const long long index_M = ist->index_M;
+    unsigned long long sum = 0ull;
+    if (tid < kSuperBlocks && blk0 + tid < nblk) {
+        const int blk = blk0 + tid;
+        if (in_circular(blk, b0, nt, nblk)) {
+            int cpos = blk / kChunkBlocks - c0;
+            if (cpos < 0) cpos += nchunk;
+            sum = touched_sum[cpos * kChunkBlocks + (blk & (kChunkBlocks - 1))];
+        } else {
+            sum = block_cum[blk] - (tid > 0 ? block_cum[blk - 1] : 0ull);
+        }
+    }
 
     // New maximum of the whole buffer: thread g answers for the four chunks 4g .. 4g+3 that
-    // partial_max[g] covers.  If one of them was touched the four are reduced again from
-    // chunk_max (and workgroup 0 stores the result); the others still have their maximum in
-    // partial_max, which nobody writes here.
+    // partial_max[g] covers.  A touched chunk has its new maximum in the four quarter maxima
+    // k_insert_patch left (workgroup 0 stores it to chunk_max, and the group's to partial_max);
+    // the others still have theirs in chunk_max / partial_max, which nobody writes here.
     uint32_t best = 0u;
     {
         const int first = 4 * tid, last = min(first + 4, nchunk);
         if (first < last) {
             const bool touched = in_circular(first, c0, nc, nchunk) || (c0 >= first && c0 < last);
             if (touched) {
-                for (int c = first; c < last; ++c) best = max(best, chunk_max[c]);
+                for (int c = first; c < last; ++c) {
+                    uint32_t m;
+                    if (in_circular(c, c0, nc, nchunk)) {
+                        m = max(max(quarter_max[4 * c], quarter_max[4 * c + 1]),
+                                max(quarter_max[4 * c + 2], quarter_max[4 * c + 3]));
+                        if (blockIdx.x == 0) chunk_max[c] = m;
+                    } else {
+                        m = chunk_max[c];
+                    }
+                    best = max(best, m);
+                }
                 if (blockIdx.x == 0) partial_max[tid] = best;
             } else {
                 best = partial_max[tid];
@@ -535,34 +574,13 @@ __global__ __launch_bounds__(1024) void k_patch_supers(const float* __restrict__
 #pragma unroll
     for (int w = 0; w < 16; ++w) wb = max(wb, wave_best[w]);
 
-    const int e = hdr->exponent;
-    const bool rebuild = ist->index_M != M || wb == 0u || exponent_of(wb) != e;
+    const bool rebuild = index_M != M || wb == 0u || exponent_of(wb) != e;
     if (rebuild) {           // the same for every thread of every workgroup
         if (blockIdx.x == 0 && tid == 0) ist->rebuild = 1u;
         return;
     }
-
-    // Block sums of this super-block: the old ones from the differences of the old prefix, the
-    // touched ones recomputed from the weights.
-    const int blk0 = s * kSuperBlocks;
-    if (tid < kSuperBlocks) {
-        const int blk = blk0 + tid;
-        unsigned long long v = 0ull;
-        if (blk < nblk) v = block_cum[blk] - (tid > 0 ? block_cum[blk - 1] : 0ull);
-        sums[tid] = v;
-    }
-    __syncthreads();
-    for (int j = 0; j < 16; ++j) {
-        const int blk = blk0 + wave * 16 + j;
-        if (blk >= nblk || !in_circular(blk, b0, nt, nblk)) continue;    // wave-uniform
-        const float4 v = load_block_quad(weights, M, blk, lane);
-        unsigned long long q = quantise(v.x, e) + quantise(v.y, e) + quantise(v.z, e) + quantise(v.w, e);
-        q = wave_sum_u64(q);
-        if (lane == 0) sums[wave * 16 + j] = q;
-    }
-    __syncthreads();
     unsigned long long total = 0ull;
-    const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
+    const unsigned long long incl = scan256(sum, wave_tot4, total);   // sum is 0 for tid >= 256
     if (tid < kSuperBlocks) {
         const int blk = blk0 + tid;
         if (blk < nblk) block_cum[blk] = incl;
@@ -839,12 +857,14 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
 
 // Large buffers and short batches are patched; everything else is inserted and rebuilt.
 constexpr int kPatchFraction = 8;   // patch when K <= M / kPatchFraction
+static_assert((kMaxChunks / kPatchFraction + 2) * kChunkBlocks <= kMaxTouched, "touched_sum holds a patch's blocks");
 
 hipError_t insert_launch(float* weights, long long M, long long cursor, const float* prio, long long K,
                          float alpha, long long* slots_out, const ReplayWs& w, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
     const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
-    if (K > 0 && nsuper >= kFusedSuperMin && K <= M / kPatchFraction) {
+    // (K <= M/8 keeps the touched chunks, at most K/4096 + 2 of them, within touched_sum)
+    if (K > 0 && nsuper >= kFusedSuperMin && K <= M / kPatchFraction && K / (kChunkBlocks * kReplayBlock) + 2 <= kMaxTouched / kChunkBlocks) {
         const int nchunk = (nblk + kChunkBlocks - 1) / kChunkBlocks;
         const int b0 = (int)(cursor / kReplayBlock);
         const int b1 = (int)(((cursor + K - 1) % M) / kReplayBlock);
@@ -854,10 +874,11 @@ hipError_t insert_launch(float* weights, long long M, long long cursor, const fl
         const int s0 = b0 / kSuperBlocks, s1 = b1 / kSuperBlocks;
         const int ns = (s1 - s0 + nsuper) % nsuper + 1;          // touched super-blocks s0, s0+1, ...
         const uint32_t* gate = &w.ist->rebuild;
-        hipLaunchKernelGGL(k_insert_patch, dim3((unsigned)nc), dim3(1024), 0, st, weights, M, nblk, nchunk, cursor,
-                           prio, K, alpha, slots_out, c0, w.hdr, w.chunk_max);
-        hipLaunchKernelGGL(k_patch_supers, dim3((unsigned)ns), dim3(1024), 0, st, weights, M, nblk, b0, nt, c0, nc,
-                           nchunk, s0, nsuper, w.hdr, w.ist, w.partial_max, w.chunk_max, w.block_cum, w.super_new);
+        hipLaunchKernelGGL(k_insert_patch, dim3((unsigned)(4 * nc)), dim3(256), 0, st, weights, M, nblk, nchunk, cursor,
+                           prio, K, alpha, slots_out, c0, w.hdr, w.quarter_max, w.touched_sum);
+        hipLaunchKernelGGL(k_patch_supers, dim3((unsigned)ns), dim3(1024), 0, st, M, nblk, b0, nt, c0, nc, nchunk, s0,
+                           nsuper, w.hdr, w.ist, w.partial_max, w.chunk_max, w.quarter_max, w.touched_sum,
+                           w.block_cum, w.super_new);
         hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
                            w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, gate);
         hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,

@@ -38,8 +38,9 @@ def test_error_codes_match_header():
 
 def test_workspace_bytes(L):
     assert b.workspace_bytes(0) == 256                       # status block only
-    # status, super-block prefixes, partial maxima, new super-block totals, per-chunk maxima
-    fixed = 256 + 2048 + 4096 + 2048 + 16384
+    # status, super-block prefixes, partial maxima, new super-block totals, chunk and quarter-chunk
+    # maxima, block sums of a patched insert
+    fixed = 256 + 2048 + 4096 + 2048 + 16384 + 65536 + 67584
     assert b.workspace_bytes(1) == fixed + 256               # one block prefix, rounded to 256
     assert b.workspace_bytes(256 * 32) == fixed + 256
     assert b.workspace_bytes(256 * 32 + 1) == fixed + 512
