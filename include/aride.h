@@ -214,8 +214,11 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
  * the buffer index advances as i <- (i + 1) mod M per entry.  The stored value is the entry's
  * sampling weight pow(max(prio[k], 0), alpha); the entry's payload belongs in the caller's own
  * arrays at the same slot, reported through slots_out.  When K > M only the last M entries
- * survive and the earlier ones report slot -1.  The sampling index is rebuilt afterwards (as
- * by aride_update_priorities with K = 0).
+ * survive and the earlier ones report slot -1.  The sampling index is current afterwards, as
+ * after aride_update_priorities with K = 0: on large buffers (M > 63 * 65536, K <= M/8) only the
+ * blocks the new entries fall into are summed again, which requires that the index in the
+ * workspace was current for these weights before the call (a workspace that never held one is
+ * recognised and built in full); otherwise the index is rebuilt.
  *
  *  weights fp32 [M] in/out (16-byte aligned); cursor in [0, M); prio fp32 [K];
  *  slots_out int64 [K] nullable; cursor_out host pointer, nullable: receives (cursor + K) mod M.
