@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
 # plain 1 GiB copy kernel.  Valid only for the kernel source it was measured on (first 16 hex
 # digits of its sha256) and for the learner-batch workload; reported as null otherwise.
-TRAFFIC = {"source_sha256": "a286ca90d1bf0384", "config": 1, "logit_rows": 82144,
-           "bytes_per_launch": 5282335213}
+TRAFFIC = {"source_sha256": "d7fbcf324c93392f", "config": 1, "logit_rows": 82144,
+           "bytes_per_launch": 5282323557}
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 
@@ -333,12 +333,8 @@ def main():
         return bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, step_logp, step_ent, si, N, R)
 
     def one_step(i, ev=None):
-        if ev is not None:
-            ev[0].record()
         b.score_logits(logits, tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
-                       step_logp=step_logp, step_ent=step_ent)
-        if ev is not None:
-            ev[1].record()
+                       step_logp=step_logp, step_ent=step_ent, sweep_events=ev)
         b.retrace_targets(step_logp, logmu, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"],
                           target=target, td=td, rho=rho)
         b.compute_priorities(td, rho, step_ent, off, cfg.w, td_scale=2.0, ent_scale=ent_scale,
@@ -349,11 +345,15 @@ def main():
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
-    # HIP events bracket the logit sweep on every 4th step only: an event costs a barrier packet
-    # on the stream, and bracketing every step would slow the very loop being timed by ~3 %
-    every = 4
+    # One pair of HIP events per timed step, attached to the dispatch of the logit sweep itself
+    # (aride_score_logits_timed): they read the kernel's own start and end, and put no marker
+    # packets on the stream.  (Events recorded around the call cost a barrier packet each and
+    # read ~30 us more than the kernel takes.)  Recording each once creates the HIP event.
     events = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for i in range(0, args.steps, every)}
+              for i in range(args.steps)}
+    for a, c in events.values():
+        a.record(); c.record()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         one_step(args.warmup + i, events.get(i))
@@ -396,7 +396,7 @@ def main():
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": B, "traj_steps": N,
                    "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
                    "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha},
-        "roofline": {"bound": "hbm", "kernel": "k_score_rows (+ k_step_sums inside the same event bracket)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "k_score_rows", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
     }

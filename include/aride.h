@@ -133,6 +133,20 @@ int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t ro
                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * score_logits_timed -- a measurement aid, the same call as aride_score_logits with two HIP
+ * events (hipEvent_t, created by the caller with timing enabled) attached to the dispatch of
+ * the row-sweep kernel itself: once the stream has drained, hipEventElapsedTime(sweep_start,
+ * sweep_stop) is that kernel's execution time, without the marker packets that recording
+ * events around the call would put on the stream.  Both events are required (E_NULL); when
+ * R == 0 nothing is launched and the events are left as they were.
+ */
+int aride_score_logits_timed(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                             const int32_t* tokens, int32_t A, float* tok_logp, float* tok_ent,
+                             float* step_logp, float* step_ent, void* ws, size_t ws_bytes,
+                             void* stream, void* sweep_start /* hipEvent_t */,
+                             void* sweep_stop /* hipEvent_t */);
+
+/*
  * retrace_targets -- Section 5.2 (Retrace(lambda) applied to the value estimate) with
  * the TD error of Section 5.3 / Appendix A.4.2.  Per trajectory, for t = T-1 .. 0:
  *     rho_t   = exp(logp_pi[t] - logp_mu[t])

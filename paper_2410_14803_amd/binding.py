@@ -20,7 +20,7 @@ ST_BAD_TOKEN, ST_BAD_WEIGHT, ST_ZERO_MASS, ST_BAD_INDEX, ST_BAD_UNIFORM = 1, 2, 
 MAX_REPLAY = 1 << 24
 
 EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
-           "aride_score_logits", "aride_retrace_targets", "aride_compute_priorities",
+           "aride_score_logits", "aride_score_logits_timed", "aride_retrace_targets", "aride_compute_priorities",
            "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns", "aride_replay_insert"]
 
 
@@ -71,6 +71,8 @@ def lib():
     L.aride_status_read.argtypes = [vp, ctypes.POINTER(Status), vp]
     L.aride_score_logits.restype = ctypes.c_int
     L.aride_score_logits.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.aride_score_logits_timed.restype = ctypes.c_int
+    L.aride_score_logits_timed.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     L.aride_retrace_targets.restype = ctypes.c_int
     L.aride_retrace_targets.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, RetraceCfg, vp, vp, vp, vp]
     L.aride_compute_priorities.restype = ctypes.c_int
@@ -134,16 +136,23 @@ class Workspace:
         return st, rc
 
 
-def score_logits(logits, tokens, A, ws, tok_logp=None, tok_ent=None, step_logp=None, step_ent=None, V=None):
-    """logits: bf16 [R, row_stride]; tokens int32 [R]; outputs are written in place."""
+def score_logits(logits, tokens, A, ws, tok_logp=None, tok_ent=None, step_logp=None, step_ent=None, V=None,
+                 sweep_events=None):
+    """logits: bf16 [R, row_stride]; tokens int32 [R]; outputs are written in place.
+    sweep_events: a pair of torch.cuda.Event(enable_timing=True), each recorded once before (which is
+    what creates the HIP event); they are attached to the row-sweep kernel's own dispatch."""
     assert logits.dtype == torch.bfloat16 and logits.dim() == 2
     R, stride = logits.shape
     V = stride if V is None else int(V)
-    rc = lib().aride_score_logits(_p(logits), R, V, stride, _p(tokens, torch.int32), int(A),
-                                  _p(tok_logp, torch.float32), _p(tok_ent, torch.float32),
-                                  _p(step_logp, torch.float32), _p(step_ent, torch.float32),
-                                  ws.ptr, ws.nbytes, _stream())
-    _check("aride_score_logits", rc)
+    args = (_p(logits), R, V, stride, _p(tokens, torch.int32), int(A),
+            _p(tok_logp, torch.float32), _p(tok_ent, torch.float32),
+            _p(step_logp, torch.float32), _p(step_ent, torch.float32), ws.ptr, ws.nbytes, _stream())
+    if sweep_events is None:
+        _check("aride_score_logits", lib().aride_score_logits(*args))
+    else:
+        e0, e1 = (ctypes.c_void_p(e.cuda_event) for e in sweep_events)
+        assert e0.value and e1.value, "record each event once before passing it"
+        _check("aride_score_logits_timed", lib().aride_score_logits_timed(*args, e0, e1))
 
 
 def retrace_targets(logp_pi, logp_mu, reward, value, traj_offsets, gamma, lam, q=None, boot=None,

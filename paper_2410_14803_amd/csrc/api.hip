@@ -5,7 +5,7 @@
 
 namespace aride {
 hipError_t score_logits_launch(const uint16_t*, long long, int, long long, const int*, int, float*,
-                               float*, float*, float*, uint32_t*, hipStream_t);
+                               float*, float*, float*, uint32_t*, hipStream_t, hipEvent_t, hipEvent_t);
 hipError_t retrace_launch(const float*, const float*, const float*, const float*, const float*,
                           const float*, const int*, int, int, float, float, int, float, float, float*, float*,
                           float*, hipStream_t);
@@ -66,9 +66,10 @@ int aride_status_read(const void* ws, aride_status* out, void* stream) {
     return ((out->flags & ARIDE_ST_ZERO_MASS) && out->total == 0) ? ARIDE_E_ZERO_MASS : ARIDE_OK;
 }
 
-int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
-                       const int32_t* tokens, int32_t A, float* tok_logp, float* tok_ent,
-                       float* step_logp, float* step_ent, void* ws, size_t ws_bytes, void* stream) {
+static int score_logits_checked(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                                const int32_t* tokens, int32_t A, float* tok_logp, float* tok_ent,
+                                float* step_logp, float* step_ent, void* ws, size_t ws_bytes, void* stream,
+                                void* sweep_start, void* sweep_stop) {
     if (R < 0 || V <= 0 || A <= 0 || row_stride < V || R % A != 0) return ARIDE_E_SHAPE;
     if (V > 0x7fffffffLL || R > (int64_t)1 << 40) return ARIDE_E_RANGE;
     if (!ws || misaligned(ws, 256)) return ARIDE_E_WORKSPACE;
@@ -80,8 +81,24 @@ int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t ro
     if (ws_bytes < kHeaderBytes) return ARIDE_E_WORKSPACE;
     hipError_t err = score_logits_launch((const uint16_t*)logits_bf16, R, (int)V, row_stride, tokens, A,
                                          tok_logp, tok_ent, step_logp, step_ent, (uint32_t*)ws,
-                                         (hipStream_t)stream);
+                                         (hipStream_t)stream, (hipEvent_t)sweep_start, (hipEvent_t)sweep_stop);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_score_logits(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                       const int32_t* tokens, int32_t A, float* tok_logp, float* tok_ent,
+                       float* step_logp, float* step_ent, void* ws, size_t ws_bytes, void* stream) {
+    return score_logits_checked(logits_bf16, R, V, row_stride, tokens, A, tok_logp, tok_ent, step_logp, step_ent,
+                                ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int aride_score_logits_timed(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,
+                             const int32_t* tokens, int32_t A, float* tok_logp, float* tok_ent,
+                             float* step_logp, float* step_ent, void* ws, size_t ws_bytes, void* stream,
+                             void* sweep_start, void* sweep_stop) {
+    if (!sweep_start || !sweep_stop) return ARIDE_E_NULL;
+    return score_logits_checked(logits_bf16, R, V, row_stride, tokens, A, tok_logp, tok_ent, step_logp, step_ent,
+                                ws, ws_bytes, stream, sweep_start, sweep_stop);
 }
 
 int aride_retrace_targets(const float* logp_pi, const float* logp_mu, const float* reward,

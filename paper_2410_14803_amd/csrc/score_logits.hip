@@ -22,6 +22,7 @@
 //    depend on how large the logits themselves are.
 //  * Per element: 1 unpack, 1/2 max3, 1/2 min3, 1 fma, 1 exp2, 1 add, 1 fma.
 #include "aride_device.h"
+#include <hip/hip_ext.h>
 
 namespace aride {
 
@@ -227,12 +228,20 @@ __global__ __launch_bounds__(256) void k_step_sums(
 }
 
 // Row sweep, then (when a per-step output is wanted) the per-step sums of the per-token arrays.
+// With events, they are attached to the dispatch of the row sweep itself: the time between
+// them is that kernel's execution time, with no marker packets on the stream around it.
 hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long long stride,
                                const int* tokens, int A, float* tok_logp, float* tok_ent,
-                               float* step_logp, float* step_ent, uint32_t* status, hipStream_t st) {
+                               float* step_logp, float* step_ent, uint32_t* status, hipStream_t st,
+                               hipEvent_t sweep_start, hipEvent_t sweep_stop) {
     const long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
-    hipLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES), 0,
-                       st, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
+    if (sweep_start || sweep_stop)
+        hipExtLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
+                              dim3(64 * ARIDE_SCORE_WAVES), 0, st, sweep_start, sweep_stop, 0, logits, R, V, stride,
+                              tokens, tok_logp, tok_ent, status);
+    else
+        hipLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES),
+                           0, st, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!step_logp && !step_ent)) return err;
     const long long N = R / A;

@@ -210,3 +210,32 @@ def test_accuracy_does_not_depend_on_the_logits_magnitude(oracle, offset):
     got, _ = run_gpu(logits, tokens, A)
     want = oracle.score_logits(bits_of(logits), npf(tokens), A)
     compare(got, want, V, A, f"offset {offset}")
+
+
+def test_timed_entry_point_gives_the_same_results_and_a_kernel_time():
+    import time
+    cfg = synth.CONFIGS[0]
+    R, V, A = 2560, cfg.V, cfg.A
+    logits = synth.logits_bf16(R, V, seed=77, device=DEV)
+    tokens = synth.action_tokens(logits, seed=78)
+    ws = b.Workspace(0)
+    f = lambda n: torch.full((n,), 7.0, device=DEV)
+    plain = [f(R), f(R), f(R // A), f(R // A)]
+    timed = [f(R), f(R), f(R // A), f(R // A)]
+    b.score_logits(logits, tokens, A, ws, *plain)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); e1.record()                       # creates the HIP events
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    b.score_logits(logits, tokens, A, ws, *timed, sweep_events=(e0, e1))
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    for p, t in zip(plain, timed):
+        assert torch.equal(p, t)
+    ms = e0.elapsed_time(e1)
+    assert 0.005 < ms <= wall_ms, (ms, wall_ms)    # 164 MB cannot be read in under 5 us
+    # both events are required
+    with pytest.raises(b.ArideError) as err:
+        b._check("aride_score_logits_timed", b.lib().aride_score_logits_timed(
+            b._p(logits), R, V, V, b._p(tokens), A, None, None, None, None, ws.ptr, ws.nbytes, None, None, None))
+    assert err.value.rc == b.E_NULL
