@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
 # plain 1 GiB copy kernel.  Valid only for the kernel source it was measured on (first 16 hex
 # digits of its sha256) and for the learner-batch workload; reported as null otherwise.
-TRAFFIC = {"source_sha256": "d7fbcf324c93392f", "config": 1, "logit_rows": 82144,
-           "bytes_per_launch": 5282323557}
+TRAFFIC = {"source_sha256": "53ae0bff741e2a75", "config": 1, "logit_rows": 82144,
+           "bytes_per_launch": 5282315764}
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 

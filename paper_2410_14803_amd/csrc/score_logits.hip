@@ -37,6 +37,9 @@ namespace aride {
 #define ARIDE_SCORE_NT 1        // 1: non-temporal loads
 #endif
 
+constexpr long long kSplitMaxRows = 4096;   // up to this many rows (4 waves per SIMD) a row is split over 4 waves
+constexpr int kSplitMinVocab = 8192;        // ... provided each wave still gets a few KB of it
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kWindow = 4.0f;      // natural-log units a group max may exceed the reference
@@ -200,6 +203,90 @@ __global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
     }
 }
 
+// The same sweep for batches of few rows, where one wave per row would leave most of the chip's
+// wave slots empty and the rows unevenly spread (2560 rows are 2.5 waves per SIMD): a workgroup
+// of four waves per row, each wave reducing a contiguous quarter of the row's 16-byte vectors
+// (wave 0 also takes the unaligned head and tail); the four (max, s, t) states meet in LDS
+// and are merged exactly as the 64 lane states are.
+template <int UNROLL>
+__global__ __launch_bounds__(256) void k_score_rows_split(
+    const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
+    const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
+    uint32_t* __restrict__ status) {
+    __shared__ float part[4][3];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long row = blockIdx.x;            // grid = R workgroups
+
+    const int tok = tokens[row];
+    const bool live = tok >= 0 && tok < V;
+    if (tok >= V && threadIdx.x == 0) atomicOr(status, 0x1u);
+
+    LaneState a;
+    lane_init(a);
+    float xtok = 0.f;
+    if (live) {
+        const uint16_t* p = logits + row * row_stride;
+        int head = (int)(((16u - (uint32_t)((uintptr_t)p & 15u)) & 15u) >> 1);
+        if (head > V) head = V;
+        const int nvec = (V - head) >> 3;
+        const int tail0 = head + (nvec << 3);
+        const u32x4* pv = reinterpret_cast<const u32x4*>(p + head);
+        const int quarter = (((nvec + 3) >> 2) + kWave - 1) & ~(kWave - 1);   // whole 1 KB pieces per wave
+        const int end = min(nvec, (wave + 1) * quarter);
+
+        int i = wave * quarter + lane;
+        for (; i + (UNROLL - 1) * kWave < end; i += UNROLL * kWave) {
+            u32x4 v[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) v[u] = load16(pv + i + u * kWave);
+            accumulate_batch<UNROLL>(a, v);
+        }
+        for (; i < end; i += kWave) {
+            u32x4 v[1] = {load16(pv + i)};
+            accumulate_batch<1>(a, v);
+        }
+        if (wave == 0) {
+            if (lane == 0) xtok = bits_to_float(((uint32_t)p[tok]) << 16);
+            if (lane < head) {
+                float x[1] = {bits_to_float(((uint32_t)p[lane]) << 16)};
+                lane_accumulate<1>(a, x);
+            }
+            if (tail0 + lane < V) {
+                float x[1] = {bits_to_float(((uint32_t)p[tail0 + lane]) << 16)};
+                lane_accumulate<1>(a, x);
+            }
+        }
+    }
+    // this wave's quarter: common reference = its exact maximum
+    const float Mw = wave_max(a.mx);
+    float s, t;
+    to_common(a.negk, a.s0 + a.s1, a.t0 + a.t1, Mw * kLog2e, s, t);
+    s = wave_sum(s);
+    t = wave_sum(t);
+    if (lane == 0) { part[wave][0] = Mw; part[wave][1] = s; part[wave][2] = t; }
+    __syncthreads();             // every wave of the workgroup gets here: nothing above returns
+
+    if (threadIdx.x == 0) {
+        float lp = 0.f, en = 0.f;
+        if (live) {
+            const float M = fmaxf(fmaxf(part[0][0], part[1][0]), fmaxf(part[2][0], part[3][0]));
+            const float kc = M * kLog2e;
+            float S = 0.f, T = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float sw, tw;
+                to_common(-(part[w][0] * kLog2e), part[w][1], part[w][2], kc, sw, tw);
+                S += sw; T += tw;
+            }
+            const float logS = logf(S);
+            lp = kLn2 * fmaf(xtok, kLog2e, -kc) - logS;
+            en = logS - kLn2 * T / S;
+        }
+        if (tok_logp) tok_logp[row] = lp;
+        if (tok_ent) tok_ent[row] = en;
+    }
+}
+
 // Per-step sums of the A per-token values: one wave per step, lanes stride over the step's
 // rows (contiguous 4-byte loads), fp64 running sums combined in a fixed butterfly order and
 // rounded to fp32 once.  log pi(a|s) of a long action is a large number whose absolute error
@@ -234,14 +321,26 @@ hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long 
                                const int* tokens, int A, float* tok_logp, float* tok_ent,
                                float* step_logp, float* step_ent, uint32_t* status, hipStream_t st,
                                hipEvent_t sweep_start, hipEvent_t sweep_stop) {
-    const long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
-    if (sweep_start || sweep_stop)
-        hipExtLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
-                              dim3(64 * ARIDE_SCORE_WAVES), 0, st, sweep_start, sweep_stop, 0, logits, R, V, stride,
-                              tokens, tok_logp, tok_ent, status);
-    else
-        hipLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES),
-                           0, st, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
+    const bool timed = sweep_start || sweep_stop;
+    if (R <= kSplitMaxRows && V >= kSplitMinVocab) {      // few long rows: four waves per row
+        if (timed)
+            hipExtLaunchKernelGGL((k_score_rows_split<ARIDE_SCORE_UNROLL>), dim3((unsigned)R), dim3(256), 0, st,
+                                  sweep_start, sweep_stop, 0, logits, R, V, stride, tokens, tok_logp, tok_ent,
+                                  status);
+        else
+            hipLaunchKernelGGL((k_score_rows_split<ARIDE_SCORE_UNROLL>), dim3((unsigned)R), dim3(256), 0, st, logits,
+                               R, V, stride, tokens, tok_logp, tok_ent, status);
+    } else {
+        const long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
+        if (timed)
+            hipExtLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
+                                  dim3(64 * ARIDE_SCORE_WAVES), 0, st, sweep_start, sweep_stop, 0, logits, R, V,
+                                  stride, tokens, tok_logp, tok_ent, status);
+        else
+            hipLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
+                               dim3(64 * ARIDE_SCORE_WAVES), 0, st, logits, R, V, stride, tokens, tok_logp, tok_ent,
+                               status);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!step_logp && !step_ent)) return err;
     const long long N = R / A;

@@ -239,3 +239,42 @@ def test_timed_entry_point_gives_the_same_results_and_a_kernel_time():
         b._check("aride_score_logits_timed", b.lib().aride_score_logits_timed(
             b._p(logits), R, V, V, b._p(tokens), A, None, None, None, None, ws.ptr, ws.nbytes, None, None, None))
     assert err.value.rc == b.E_NULL
+
+
+@pytest.mark.parametrize("V,stride_pad", [(8192, 0), (8193, 3), (8199, 1), (12345, 5), (16384 + 511, 2), (65536, 0)])
+def test_four_waves_per_row_path(oracle, V, stride_pad):
+    # few rows of a long vocabulary: each row is split over the four waves of a workgroup
+    print(f"case V={V} pad={stride_pad}", flush=True)
+    N, A = 5, 3
+    R = N * A
+    stride = V + stride_pad
+    full = synth.logits_bf16(R, stride, seed=900 + V, device=DEV, heavy_tail=True)
+    q = V // 4
+    full[1, :q] = float("-inf")                      # a whole quarter masked out
+    full[2, q:2 * q] = float("-inf")
+    full[3, 3 * q:V] = -3.0e38                       # ... or hugely negative
+    for r, col in ((4, 5), (5, q + 77), (6, 2 * q + 1), (7, V - 1)):
+        full[r, col] = 60.0                          # a dominant logit in each quarter in turn
+    tokens = synth.action_tokens(full[:, :V].float().clamp(min=-1e30).to(torch.bfloat16).contiguous(), seed=901 + V)
+    tokens[4], tokens[5], tokens[6], tokens[7] = 5, q + 77, 2 * q + 1, 0
+    tokens[8] = -1
+    tokens[9] = V                                     # out of range: masked, flagged
+    got, flags = run_gpu(full, tokens, A, V=V)
+    tok_o = npf(tokens).copy()
+    tok_o[9] = -1
+    want = oracle.score_logits(bits_of(full), tok_o, A, V=V)
+    compare(got, want, V, A, f"split V={V}")
+    assert flags == b.ST_BAD_TOKEN
+    assert got["tok_logp"][8] == 0 and got["tok_ent"][8] == 0 and got["tok_logp"][9] == 0
+
+
+def test_both_sweeps_agree_at_the_row_count_where_they_switch(oracle):
+    V = 9000
+    logits = synth.logits_bf16(4097, V, seed=950, device=DEV)
+    tokens = synth.action_tokens(logits, seed=951)
+    a, _ = run_gpu(logits[:4096].contiguous(), tokens[:4096].contiguous(), 1)     # four waves per row
+    c, _ = run_gpu(logits, tokens, 1)                                             # one wave per row
+    want = oracle.score_logits(bits_of(logits), npf(tokens), 1, nthreads=8)
+    for k in ("tok_logp", "tok_ent"):
+        assert_close(c[k], want[k], 1.0 if k == "tok_logp" else ent_floor(V), f"one wave per row {k}")
+        assert_close(a[k], want[k][:4096], 1.0 if k == "tok_logp" else ent_floor(V), f"four waves per row {k}")
