@@ -69,6 +69,13 @@ def test_score_logits_rejects_bad_arguments(L):
     assert f(x, 4, 10, 10, t, 1, None, None, P(64), None, ws, 256, None) == b.E_NULL    # step sums need tok arrays
     assert f(x, 4, 10, 10, t, 1, P(64), None, None, P(64), ws, 256, None) == b.E_NULL
     assert f(x, 0, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.OK         # empty: no-op
+    # the timed variant: both events are required, then the same validation
+    g = L.aride_score_logits_timed
+    ev = P(4096)
+    assert g(x, 4, 10, 10, t, 1, None, None, None, None, ws, 256, None, None, ev) == b.E_NULL
+    assert g(x, 4, 10, 10, t, 1, None, None, None, None, ws, 256, None, ev, None) == b.E_NULL
+    assert g(x, 4, 10, 10, t, 3, None, None, None, None, ws, 256, None, ev, ev) == b.E_SHAPE
+    assert g(x, 0, 10, 10, t, 1, None, None, None, None, ws, 256, None, ev, ev) == b.OK
 
 
 def test_retrace_and_priorities_reject_bad_arguments(L):
