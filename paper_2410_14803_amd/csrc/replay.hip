@@ -743,6 +743,11 @@ __global__ __launch_bounds__(256) void k_sample(
     const unsigned long long* __restrict__ block_cum, int nblk,
     const unsigned long long* __restrict__ super_cum, const double* __restrict__ uniforms,
     int K, long long* __restrict__ idx_out, float* __restrict__ prob_out, uint32_t* __restrict__ flags) {
+    // The 256 super-block prefixes are the same for every draw: one load per thread brings them
+    // into LDS, which takes the first level's two dependent probes off the global-memory path.
+    __shared__ unsigned long long super_lds[kSuperBlocks];
+    super_lds[threadIdx.x] = super_cum[threadIdx.x];
+    __syncthreads();                                 // before any wave may leave
     const int lane = threadIdx.x & 63, group = lane >> 4, gl = lane & 15;
     const int wave_id = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     if (wave_id * 4 >= K) return;                    // whole waves leave together
@@ -763,7 +768,7 @@ __global__ __launch_bounds__(256) void k_sample(
 
     // level 1: first super-block whose inclusive prefix exceeds t (the padding equals Total > t)
     unsigned long long before;
-    const int sblk = search256(super_cum, kSuperBlocks, t, group, gl, before);
+    const int sblk = search256(super_lds, kSuperBlocks, t, group, gl, before);
     bool stale = sblk >= kSuperBlocks;               // cannot happen with a current index
     unsigned long long rem = t - (stale ? 0ull : before);
     // level 2: first block of that super-block whose inclusive prefix exceeds the remainder
@@ -804,19 +809,22 @@ __global__ __launch_bounds__(256) void k_sample(
     if (stale || owner >= 16) {
         if (live && gl == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
     } else if (live && gl == owner) {
+        // the running totals inside the lane never decrease, so the entry hit is the number of
+        // them that have not passed rem (the 16th has, or this lane would not be the owner)
         unsigned long long c = incl - mine;
         int j = 0;
 #pragma unroll
         for (int i = 0; i < 15; ++i) {
-            const bool pass = (j == i) && (c + q[i] <= rem);
-            c += pass ? q[i] : 0ull;
-            j += pass ? 1 : 0;
+            c += q[i];
+            j += (c <= rem) ? 1 : 0;
         }
-        unsigned long long qj = q[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) qj = (j == i) ? q[i] : qj;
         idx_out[k] = base + j;
-        if (prob_out) prob_out[k] = (float)((double)qj / (double)total);
+        if (prob_out) {
+            unsigned long long qj = q[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) qj = (j == i) ? q[i] : qj;
+            prob_out[k] = (float)((double)qj / (double)total);
+        }
     }
 }
 
