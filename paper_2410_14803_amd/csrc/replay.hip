@@ -8,9 +8,19 @@
 // The index kept in the workspace has two levels: blocks of 256 weights (one wave x float4)
 // and super-blocks of 256 blocks.  block_cum holds, per super-block, the inclusive prefix of
 // its block sums; super_cum holds the inclusive prefix of the super-block totals (padded to
-// 256 entries with Total).  A draw needs three dependent reads: all 256 entries of
-// super_cum at once (4 per lane, counted with ballots), the 256 block prefixes of the chosen
-// super-block the same way, then one 1 KB block of weights with a wave-wide integer scan.
+// 256 entries with Total).  A draw is served by 16 lanes: the 256 super-block prefixes (staged
+// in LDS) and the 256 block prefixes of the chosen super-block are each searched 16-ary in two
+// probes, then the lanes quantise and scan the chosen block's 256 weights.
+//
+// Keeping the index current:
+//  * a rebuild of a large buffer is ONE sweep (k_super_sums<true>): it finds the maxima and
+//    sums under the exponent of the index as it stands; k_super_sums<false> sweeps again only
+//    if the maximum's exponent has moved.  Smaller buffers take a maximum pass, a block-sum
+//    pass and a scan; the smallest do everything in one workgroup.
+//  * alongside, the largest valid weight of every chunk of 16 blocks (chunk_max) and of every
+//    four chunks (partial_max) is kept, so that after a contiguous insert the new maximum of the
+//    whole buffer follows from the touched chunks alone and the index can be patched
+//    (k_insert_patch, k_patch_supers, k_patch_finish) instead of rebuilt.
 //
 // update_priorities resolves repeated indices without a serial loop: pass 1 writes the
 // tag (0xFF800000 | k) with an unsigned atomic max into the weight slot itself -- every
