@@ -83,3 +83,70 @@ def test_hot_path_in_a_hip_graph():
                                           err_msg=f"replay {rep}: {k} differs from the eager run")
     st, rc = ws.status()
     assert rc == b.OK and st.flags == 0
+
+
+def test_large_buffer_rebuild_and_patched_insert_in_a_hip_graph(oracle):
+    # Whether a rebuild needs its second sweep, and whether an insert can be patched, is decided
+    # on the device: a captured graph must take the right route for every input it is replayed on.
+    M = 64 * 65536 + 3 * 256 + 9
+    K_up, K_in, K_s, cursor = 5000, 3000, 600, M - 1000
+    w0_host = np.zeros(M, np.float32)
+    oracle.update_priorities(w0_host, np.arange(M), npf(synth.replay_priorities(M, "lognormal", 3, "cpu")), 0.6)
+    w0 = torch.as_tensor(w0_host, device=DEV)
+    weights = w0.clone()
+    ws = b.Workspace(M)
+    idx_up = torch.zeros(K_up, dtype=torch.int64, device=DEV)
+    p_up = torch.zeros(K_up, device=DEV)
+    p_in = torch.zeros(K_in, device=DEV)
+    u = torch.zeros(K_s, dtype=torch.float64, device=DEV)
+    drawn = [torch.zeros(K_s, dtype=torch.int64, device=DEV) for _ in range(2)]
+
+    def chain():
+        b.update_priorities(weights, idx_up, p_up, 0.6, ws)
+        b.sample_prioritized(weights, u, ws, drawn[0], None)
+        b.replay_insert(weights, cursor, p_in, 0.6, ws)
+        b.sample_prioritized(weights, u, ws, drawn[1], None)
+
+    def set_inputs(seed, up_scale, in_scale):
+        rng = np.random.default_rng(seed)
+        idx_up.copy_(torch.as_tensor(rng.integers(0, M, K_up), device=DEV))
+        p_up.copy_(torch.as_tensor((rng.random(K_up) * up_scale).astype(np.float32), device=DEV))
+        p_in.copy_(torch.as_tensor((rng.random(K_in) * in_scale).astype(np.float32), device=DEV))
+        u.copy_(synth.uniforms(K_s, seed, DEV))
+        weights.copy_(w0)
+        b.update_priorities(weights, None, None, 0.6, ws)
+        torch.cuda.synchronize()
+
+    def check(tag):
+        torch.cuda.synchronize()
+        oi, _, _ = oracle.sample_prioritized(npf(weights), npf(u))
+        np.testing.assert_array_equal(npf(drawn[1]), oi, err_msg=tag)
+        st, rc = ws.status()
+        _, total = oracle.quantise_weights(npf(weights))
+        assert rc == b.OK and st.total == total, tag
+        return npf(weights).copy(), npf(drawn[0]).copy()
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        set_inputs(1, 1.0, 1.0)
+        chain()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    set_inputs(1, 1.0, 1.0)
+    with torch.cuda.graph(g):
+        chain()
+    # (update scale, insert scale): same exponent throughout / the update raises it / the insert
+    # raises it / back to the first
+    for rep, (up_scale, in_scale) in enumerate([(1.0, 1.0), (1e6, 1.0), (1.0, 1e6), (1.0, 1.0)]):
+        set_inputs(20 + rep, up_scale, in_scale)
+        chain()
+        eager = check(f"eager {rep}")
+        for d in drawn:
+            d.fill_(-5)
+        set_inputs(20 + rep, up_scale, in_scale)
+        g.replay()
+        replayed = check(f"replay {rep}")
+        np.testing.assert_array_equal(eager[0], replayed[0])
+        np.testing.assert_array_equal(eager[1], replayed[1])
