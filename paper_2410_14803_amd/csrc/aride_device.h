@@ -19,6 +19,8 @@ constexpr int kWave = 64;
 //   then                      quarter_max: maxima of the quarter chunks (4 blocks) an insert has just
 //                             touched, handed from its first step to its second (16384 x u32)
 //   then                      touched_sum: integer sums of the blocks of those chunks, by position (8448 x u64)
+//   then                      sub_sum: integer sum of every sub-block of 16 weights (16*nblk x u64), the
+//                             third level of the index
 struct WsHeader {
     uint32_t flags;      // OR of status bits
     uint32_t reserved;
@@ -45,6 +47,8 @@ constexpr size_t kChunkBytes = kMaxChunks * 4;
 constexpr size_t kQuarterBytes = 4 * kChunkBytes;
 constexpr int kMaxTouched = 8448;  // blocks of the chunks one patched insert may touch
 constexpr size_t kTouchedBytes = kMaxTouched * 8;
+constexpr int kSubBlock = 16;      // weights per sub-block: what the 16 lanes serving a draw quantise
+constexpr int kSubsPerBlock = kReplayBlock / kSubBlock;
 
 // The arrays of the replay index inside a workspace sized for capacity M.
 struct ReplayWs {
@@ -57,13 +61,15 @@ struct ReplayWs {
     uint32_t* chunk_max;
     uint32_t* quarter_max;
     unsigned long long* touched_sum;
+    unsigned long long* sub_sum;
 };
 inline size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
 inline size_t replay_blocks(long long M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
 inline size_t replay_index_bytes(long long M) {
     if (M <= 0) return 0;
     const size_t nblk = replay_blocks(M);
-    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes;
+    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes +
+           round_up_256(nblk * kSubsPerBlock * 8);
 }
 inline ReplayWs replay_ws(void* ws, long long M) {
     char* p = static_cast<char*>(ws);
@@ -79,6 +85,7 @@ inline ReplayWs replay_ws(void* ws, long long M) {
     w.chunk_max = reinterpret_cast<uint32_t*>(after + kSuperBytes);
     w.quarter_max = reinterpret_cast<uint32_t*>(after + kSuperBytes + kChunkBytes);
     w.touched_sum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes);
+    w.sub_sum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes);
     return w;
 }
 

@@ -241,10 +241,56 @@ __device__ __forceinline__ unsigned long long scan256(unsigned long long v, unsi
     return before + incl;
 }
 
+// Cross-lane moves inside a row of 16 lanes as DPP operands of ordinary vector instructions
+// (no trip through the LDS crossbar, which is what __shfl costs).  CTRL: 0x110 | n shifts the
+// row right by n lanes (lanes without a source read 0), 0x120 | n rotates it, 0x00..0xFF permute
+// each quad of lanes.
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), CTRL, 0xF, 0xF, true);
+    return ((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E;   // quad_perm [1,0,3,2] and [2,3,0,1]
+
+// Sum over each quad of lanes -- 16 consecutive weights, a sub-block, when every lane holds four
+// -- left in all four lanes; the quad's first lane stores it as the sub-block's entry.
+__device__ __forceinline__ unsigned long long quad_sum_u64(unsigned long long v) {
+    v += dpp_u64<kDppQuadXor1>(v);
+    v += dpp_u64<kDppQuadXor2>(v);
+    return v;
+}
+// Sum over a row of 16 lanes, left in all of them: rotations by 8, 4, 2, 1 (by 8 and 4 only when
+// the four lanes of every quad already hold the same value, which is then counted once).
+template <bool QUADS>
+__device__ __forceinline__ unsigned long long row_sum_u64(unsigned long long v) {
+    v += dpp_u64<0x128>(v);
+    v += dpp_u64<0x124>(v);
+    if constexpr (!QUADS) {
+        v += dpp_u64<0x122>(v);
+        v += dpp_u64<0x121>(v);
+    }
+    return v;
+}
+// Inclusive scan along a row of 16 lanes.
+__device__ __forceinline__ unsigned long long row_scan_u64(unsigned long long v) {
+    v += dpp_u64<0x111>(v);
+    v += dpp_u64<0x112>(v);
+    v += dpp_u64<0x114>(v);
+    v += dpp_u64<0x118>(v);
+    return v;
+}
+__device__ __forceinline__ void store_sub_sum(unsigned long long* __restrict__ sub_sum, int blk, int lane,
+                                              unsigned long long quad) {
+    if ((lane & 3) == 0) sub_sum[(long long)blk * kSubsPerBlock + (lane >> 2)] = quad;
+}
+
 // Four wave-wide sums at once: in each of two exchange rounds a lane hands half of its partial
 // sums to the partner lane and keeps the other half (the number of live values halves, the
-// number of lanes sharing each doubles); four more rounds finish the one value left.
+// number of lanes sharing each doubles); more rounds finish the one value left -- four, or
+// two when the inputs are quad sums already (QUADS: each value counted once per quad).
 // Returns, in lane L, the wave-wide sum of part[L >> 4] (7 shuffles instead of 24).
+template <bool QUADS = false>
 __device__ __forceinline__ unsigned long long transposed_sum4(unsigned long long (&part)[4], int lane) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
@@ -257,9 +303,7 @@ __device__ __forceinline__ unsigned long long transposed_sum4(unsigned long long
             part[i] = keep + __shfl_xor(send, mask, kWave);
         }
     }
-#pragma unroll
-    for (int d = 8; d >= 1; d >>= 1) part[0] += __shfl_xor(part[0], d, kWave);
-    return part[0];
+    return row_sum_u64<QUADS>(part[0]);
 }
 
 // quantise for a guessed exponent: a weight above 2^e would leave the range the conversions
@@ -291,6 +335,7 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
                                                      uint32_t* __restrict__ chunk_max,
                                                      unsigned long long* __restrict__ block_cum, int nblk,
                                                      unsigned long long* __restrict__ super_raw,
+                                                     unsigned long long* __restrict__ sub_sum,
                                                      const uint32_t* __restrict__ gate) {
     __shared__ unsigned long long sums[kSuperBlocks];
     __shared__ unsigned long long wave_tot4[4];
@@ -354,8 +399,15 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
                           quantise_capped(w.w, e);
             else
                 part[j] = quantise(w.x, e) + quantise(w.y, e) + quantise(w.z, e) + quantise(w.w, e);
+            part[j] = quad_sum_u64(part[j]);
         }
-        const unsigned long long sum = transposed_sum4(part, lane);
+        {   // one store for the four blocks: lane 4i + r writes sub-block i of block 4g + r
+            const int r = lane & 3;
+            const unsigned long long mine = r == 0 ? part[0] : r == 1 ? part[1] : r == 2 ? part[2] : part[3];
+            const int blk = blk_first + 4 * g + r;
+            if (blk < nblk) sub_sum[(long long)blk * kSubsPerBlock + (lane >> 2)] = mine;
+        }
+        const unsigned long long sum = transposed_sum4<true>(part, lane);
         if ((lane & 15) == 0) sums[wave * 16 + 4 * g + (lane >> 4)] = sum;
     }
     __syncthreads();
@@ -377,7 +429,8 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
 // chip idle: integer sum of each block of 256 weights, one wave per block, raw sums to block_cum.
 __global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ weights, long long M,
                                                     const uint32_t* __restrict__ partial_max,
-                                                    unsigned long long* __restrict__ block_cum, int nblk) {
+                                                    unsigned long long* __restrict__ block_cum, int nblk,
+                                                    unsigned long long* __restrict__ sub_sum) {
     __shared__ uint32_t wave_best[4];
     const int lane = threadIdx.x & 63;
     const int blk = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
@@ -394,6 +447,7 @@ __global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ we
             for (int j = 0; j < 4; ++j) if (base + j < M) q += quantise(weights[base + j], e);
         }
     }
+    store_sub_sum(sub_sum, blk, lane, quad_sum_u64(q));
     q = wave_sum_u64(q);
     if (lane == 0) block_cum[blk] = q;
 }
@@ -472,7 +526,8 @@ __global__ __launch_bounds__(256) void k_insert_patch(float* __restrict__ weight
                                                       long long cursor, const float* __restrict__ prio, long long K,
                                                       float alpha, long long* __restrict__ slots_out, int c0,
                                                       WsHeader* hdr, uint32_t* __restrict__ quarter_max,
-                                                      unsigned long long* __restrict__ touched_sum) {
+                                                      unsigned long long* __restrict__ touched_sum,
+                                                      unsigned long long* __restrict__ sub_sum) {
     __shared__ uint32_t wave_best[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int chunk = c0 + (int)(blockIdx.x >> 2);     // the touched chunks c0, c0+1, ... (circular)
@@ -503,8 +558,10 @@ __global__ __launch_bounds__(256) void k_insert_patch(float* __restrict__ weight
         best = wave_max_u32(quad_max_bits(make_float4(w[0], w[1], w[2], w[3]), bad));
         // the block's integer sum under the standing exponent, a guess that k_patch_supers checks
         const int e = hdr->exponent;
-        const unsigned long long q = wave_sum_u64(quantise_capped(w[0], e) + quantise_capped(w[1], e) +
-                                                  quantise_capped(w[2], e) + quantise_capped(w[3], e));
+        const unsigned long long mine = quantise_capped(w[0], e) + quantise_capped(w[1], e) +
+                                        quantise_capped(w[2], e) + quantise_capped(w[3], e);
+        store_sub_sum(sub_sum, blk, lane, quad_sum_u64(mine));    // stands if the guess does; else all are rewritten
+        const unsigned long long q = wave_sum_u64(mine);
         if (lane == 0) touched_sum[4 * blockIdx.x + wave] = q;    // by position: block 16*c0 is entry 0
     }
     const bool any_bad = __any(bad);
@@ -639,7 +696,7 @@ constexpr int kFusedSuperMin = 64;      // from this many super-blocks on, one w
 __global__ __launch_bounds__(1024) void k_update_small(
     float* __restrict__ weights, int M, const long long* __restrict__ idx, const float* __restrict__ prio,
     int K, float alpha, WsHeader* hdr, WsIndexState* ist, unsigned long long* __restrict__ block_cum, int nblk,
-    unsigned long long* __restrict__ super_cum) {
+    unsigned long long* __restrict__ super_cum, unsigned long long* __restrict__ sub_sum) {
     __shared__ unsigned long long sums[1024];
     __shared__ unsigned long long wave_tot[16];
     __shared__ uint32_t wave_max_bits[16];
@@ -693,6 +750,7 @@ __global__ __launch_bounds__(1024) void k_update_small(
                     q += quantise(bits_to_float(__hip_atomic_load(wbits + base + j, __ATOMIC_RELAXED,
                                                                   __HIP_MEMORY_SCOPE_AGENT)), e);
         }
+        store_sub_sum(sub_sum, blk, lane, quad_sum_u64(q));
         q = wave_sum_u64(q);
         if (lane == 0) sums[blk] = q;
     }
@@ -751,8 +809,9 @@ __device__ __forceinline__ int search256(const unsigned long long* __restrict__ 
 __global__ __launch_bounds__(256) void k_sample(
     const float* __restrict__ weights, long long M, const WsHeader* __restrict__ hdr,
     const unsigned long long* __restrict__ block_cum, int nblk,
-    const unsigned long long* __restrict__ super_cum, const double* __restrict__ uniforms,
-    int K, long long* __restrict__ idx_out, float* __restrict__ prob_out, uint32_t* __restrict__ flags) {
+    const unsigned long long* __restrict__ super_cum, const unsigned long long* __restrict__ sub_sum,
+    const double* __restrict__ uniforms, int K, long long* __restrict__ idx_out, float* __restrict__ prob_out,
+    uint32_t* __restrict__ flags) {
     // The 256 super-block prefixes are the same for every draw: one load per thread brings them
     // into LDS, which takes the first level's two dependent probes off the global-memory path.
     __shared__ unsigned long long super_lds[kSuperBlocks];
@@ -788,53 +847,27 @@ __global__ __launch_bounds__(256) void k_sample(
     const int blk = stale ? 0 : first + within;
     rem -= stale ? 0ull : before;
 
-    // level 3: the block's 256 weights, 16 consecutive ones per lane
-    const int e = exponent_of(hdr->wmax_bits);
-    const long long base = (long long)blk * kReplayBlock + gl * 16;
-    unsigned long long q[16];
-#pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-        const long long b4 = base + 4 * v4;
-        float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (b4 + 3 < M) w = *reinterpret_cast<const float4*>(weights + b4);
-        else if (b4 < M) {
-            w.x = weights[b4];
-            if (b4 + 1 < M) w.y = weights[b4 + 1];
-            if (b4 + 2 < M) w.z = weights[b4 + 2];
-        }
-        q[4 * v4 + 0] = quantise(w.x, e); q[4 * v4 + 1] = quantise(w.y, e);
-        q[4 * v4 + 2] = quantise(w.z, e); q[4 * v4 + 3] = quantise(w.w, e);
-    }
-    unsigned long long mine = 0ull;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) mine += q[j];
-    unsigned long long incl = mine;
-#pragma unroll
-    for (int d = 1; d < 16; d <<= 1) {               // inclusive scan inside the group of 16 lanes
-        const unsigned long long up = __shfl_up(incl, d, 16);
-        if (gl >= d) incl += up;
-    }
-    const int owner = group_count(incl <= rem, group);   // lanes whose running total has not passed rem yet
+    // level 3: the block's 16 sub-block sums, one per lane; the sub-block whose running total
+    // first passes the remainder is the one hit
+    const unsigned long long sub = sub_sum[(long long)blk * kSubsPerBlock + gl];
+    const unsigned long long sub_incl = row_scan_u64(sub);       // the 16 lanes of a draw are one DPP row
+    const int owner_sub = group_count(sub_incl <= rem, group);   // lanes whose running total has not passed rem yet
     // a stale index (weights changed without a rebuild) can run past the end: report -1
-    if (stale || owner >= 16) {
+    stale = stale || owner_sub >= kSubsPerBlock;
+    const int hit = stale ? 0 : owner_sub;
+    rem -= stale ? 0ull : __shfl(sub_incl - sub, 16 * group + hit, kWave);
+
+    // level 4: the sub-block's 16 weights, one per lane
+    const int e = exponent_of(hdr->wmax_bits);
+    const long long slot = (long long)blk * kReplayBlock + hit * kSubBlock + gl;
+    const unsigned long long q = quantise(slot < M ? weights[slot] : 0.f, e);
+    const unsigned long long q_incl = row_scan_u64(q);
+    const int owner = group_count(q_incl <= rem, group);
+    if (stale || owner >= kSubBlock) {
         if (live && gl == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
     } else if (live && gl == owner) {
-        // the running totals inside the lane never decrease, so the entry hit is the number of
-        // them that have not passed rem (the 16th has, or this lane would not be the owner)
-        unsigned long long c = incl - mine;
-        int j = 0;
-#pragma unroll
-        for (int i = 0; i < 15; ++i) {
-            c += q[i];
-            j += (c <= rem) ? 1 : 0;
-        }
-        idx_out[k] = base + j;
-        if (prob_out) {
-            unsigned long long qj = q[0];
-#pragma unroll
-            for (int i = 1; i < 16; ++i) qj = (j == i) ? q[i] : qj;
-            prob_out[k] = (float)((double)qj / (double)total);
-        }
+        idx_out[k] = slot;
+        if (prob_out) prob_out[k] = (float)((double)q / (double)total);
     }
 }
 
@@ -844,7 +877,7 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
     if (M <= kSmallReplay && K <= kSmallBatch) {
         hipLaunchKernelGGL(k_update_small, dim3(1), dim3(1024), 0, st, weights, (int)M, idx, prio, K, alpha,
-                           w.hdr, w.ist, w.block_cum, nblk, w.super_cum);
+                           w.hdr, w.ist, w.block_cum, nblk, w.super_cum, w.sub_sum);
         return hipGetLastError();
     }
     if (K > 0 && K <= kSmallBatch) {
@@ -857,14 +890,14 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     if (nsuper >= kFusedSuperMin) {
         const uint32_t* always = nullptr;
         hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, always);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, always);
         hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, always);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, always);
     } else {
         hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, nblk, w.hdr, w.partial_max,
                            w.chunk_max, (const uint32_t*)nullptr);
         hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M,
-                           w.partial_max, w.block_cum, nblk);
+                           w.partial_max, w.block_cum, nblk, w.sub_sum);
         hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, w.block_cum, nblk, w.super_cum,
                            w.partial_max, w.hdr, w.ist, M);
         if (nsuper == 1) return hipGetLastError();   // the scan kernel finalised the index itself
@@ -893,14 +926,14 @@ hipError_t insert_launch(float* weights, long long M, long long cursor, const fl
         const int ns = (s1 - s0 + nsuper) % nsuper + 1;          // touched super-blocks s0, s0+1, ...
         const uint32_t* gate = &w.ist->rebuild;
         hipLaunchKernelGGL(k_insert_patch, dim3((unsigned)(4 * nc)), dim3(256), 0, st, weights, M, nblk, nchunk, cursor,
-                           prio, K, alpha, slots_out, c0, w.hdr, w.quarter_max, w.touched_sum);
+                           prio, K, alpha, slots_out, c0, w.hdr, w.quarter_max, w.touched_sum, w.sub_sum);
         hipLaunchKernelGGL(k_patch_supers, dim3((unsigned)ns), dim3(1024), 0, st, M, nblk, b0, nt, c0, nc, nchunk, s0,
                            nsuper, w.hdr, w.ist, w.partial_max, w.chunk_max, w.quarter_max, w.touched_sum,
                            w.block_cum, w.super_new);
         hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, gate);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, gate);
         hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, gate);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, gate);
         hipLaunchKernelGGL(k_patch_finish, dim3(1), dim3(256), 0, st, w.super_cum, w.super_new, nsuper, s0, ns,
                            w.partial_max, w.hdr, w.ist, M);
         return hipGetLastError();
@@ -917,7 +950,7 @@ hipError_t sample_launch(const float* weights, long long M, const ReplayWs& w, c
     const long long waves = ((long long)K + 3) / 4;      // four draws per wave
     const unsigned g = (unsigned)((waves * kWave + 255) / 256);
     hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, w.hdr, w.block_cum, nblk, w.super_cum,
-                       uniforms, K, idx_out, prob_out, &w.hdr->flags);
+                       w.sub_sum, uniforms, K, idx_out, prob_out, &w.hdr->flags);
     return hipGetLastError();
 }
 

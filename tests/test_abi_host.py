@@ -41,10 +41,11 @@ def test_workspace_bytes(L):
     # status, super-block prefixes, partial maxima, new super-block totals, chunk and quarter-chunk
     # maxima, block sums of a patched insert
     fixed = 256 + 2048 + 4096 + 2048 + 16384 + 65536 + 67584
-    assert b.workspace_bytes(1) == fixed + 256               # one block prefix, rounded to 256
-    assert b.workspace_bytes(256 * 32) == fixed + 256
-    assert b.workspace_bytes(256 * 32 + 1) == fixed + 512
-    assert b.workspace_bytes(1 << 24) == fixed + 8 * 65536
+    # per block of 256 weights: one u64 prefix and 16 u64 sub-block sums, each array rounded to 256 bytes
+    assert b.workspace_bytes(1) == fixed + 256 + 256
+    assert b.workspace_bytes(256 * 32) == fixed + 256 + 32 * 128
+    assert b.workspace_bytes(256 * 32 + 1) == fixed + 512 + 4352
+    assert b.workspace_bytes(1 << 24) == fixed + 8 * 65536 + 128 * 65536
     out = ctypes.c_size_t(0)
     assert L.aride_workspace_bytes(-1, ctypes.byref(out)) == b.E_SHAPE
     assert L.aride_workspace_bytes((1 << 24) + 1, ctypes.byref(out)) == b.E_RANGE
