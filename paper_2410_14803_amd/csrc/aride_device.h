@@ -19,6 +19,8 @@ constexpr int kWave = 64;
 //   then                      quarter_max: maxima of the quarter chunks (4 blocks) an insert has just
 //                             touched, handed from its first step to its second (16384 x u32)
 //   then                      touched_sum: integer sums of the blocks of those chunks, by position (8448 x u64)
+//   then                      coarse_cum: every 16th entry of block_cum (entries 15, 31, .. of each super-block's
+//                             run), 16 per super-block, contiguous: the first probe of a draw (256 x 16 x u64)
 //   then                      sub_sum: integer sum of every sub-block of 16 weights (16*nblk x u64), the
 //                             third level of the index
 struct WsHeader {
@@ -49,6 +51,7 @@ constexpr int kMaxTouched = 8448;  // blocks of the chunks one patched insert ma
 constexpr size_t kTouchedBytes = kMaxTouched * 8;
 constexpr int kSubBlock = 16;      // weights per sub-block: what the 16 lanes serving a draw quantise
 constexpr int kSubsPerBlock = kReplayBlock / kSubBlock;
+constexpr size_t kCoarseBytes = kSuperBlocks * 16 * 8;
 
 // The arrays of the replay index inside a workspace sized for capacity M.
 struct ReplayWs {
@@ -62,13 +65,14 @@ struct ReplayWs {
     uint32_t* quarter_max;
     unsigned long long* touched_sum;
     unsigned long long* sub_sum;
+    unsigned long long* coarse_cum;
 };
 inline size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
 inline size_t replay_blocks(long long M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
 inline size_t replay_index_bytes(long long M) {
     if (M <= 0) return 0;
     const size_t nblk = replay_blocks(M);
-    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes +
+    return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes + kCoarseBytes +
            round_up_256(nblk * kSubsPerBlock * 8);
 }
 inline ReplayWs replay_ws(void* ws, long long M) {
@@ -85,7 +89,9 @@ inline ReplayWs replay_ws(void* ws, long long M) {
     w.chunk_max = reinterpret_cast<uint32_t*>(after + kSuperBytes);
     w.quarter_max = reinterpret_cast<uint32_t*>(after + kSuperBytes + kChunkBytes);
     w.touched_sum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes);
-    w.sub_sum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes);
+    w.coarse_cum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes);
+    w.sub_sum = reinterpret_cast<unsigned long long*>(after + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes +
+                                                      kCoarseBytes);
     return w;
 }
 

@@ -280,6 +280,12 @@ __device__ __forceinline__ unsigned long long row_scan_u64(unsigned long long v)
     v += dpp_u64<0x118>(v);
     return v;
 }
+// Every 16th entry of a super-block's prefix is kept a second time, contiguously: a draw's first
+// probe then reads one 128-byte line instead of 16 lines 128 bytes apart.
+__device__ __forceinline__ void store_coarse(unsigned long long* __restrict__ coarse_cum, int sblk, int pos,
+                                             unsigned long long incl) {
+    if ((pos & 15) == 15) coarse_cum[sblk * 16 + (pos >> 4)] = incl;
+}
 __device__ __forceinline__ void store_sub_sum(unsigned long long* __restrict__ sub_sum, int blk, int lane,
                                               unsigned long long quad) {
     if ((lane & 3) == 0) sub_sum[(long long)blk * kSubsPerBlock + (lane >> 2)] = quad;
@@ -336,6 +342,7 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
                                                      unsigned long long* __restrict__ block_cum, int nblk,
                                                      unsigned long long* __restrict__ super_raw,
                                                      unsigned long long* __restrict__ sub_sum,
+                                                     unsigned long long* __restrict__ coarse_cum,
                                                      const uint32_t* __restrict__ gate) {
     __shared__ unsigned long long sums[kSuperBlocks];
     __shared__ unsigned long long wave_tot4[4];
@@ -420,7 +427,7 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
     const unsigned long long incl = scan256(tid < kSuperBlocks ? sums[tid] : 0ull, wave_tot4, total);
     if (tid < kSuperBlocks) {
         const int blk = sblk * kSuperBlocks + tid;
-        if (blk < nblk) block_cum[blk] = incl;
+        if (blk < nblk) { block_cum[blk] = incl; store_coarse(coarse_cum, sblk, tid, incl); }
         if (tid == 0) super_raw[sblk] = total;
     }
 }
@@ -457,13 +464,14 @@ __global__ __launch_bounds__(256) void k_block_sums(const float* __restrict__ we
 __global__ __launch_bounds__(256) void k_scan_supers(unsigned long long* __restrict__ block_cum, int nblk,
                                                      unsigned long long* __restrict__ super_raw,
                                                      const uint32_t* __restrict__ partial_max, WsHeader* hdr,
-                                                     WsIndexState* ist, long long M) {
+                                                     WsIndexState* ist, long long M,
+                                                     unsigned long long* __restrict__ coarse_cum) {
     __shared__ unsigned long long wave_tot4[4];
     __shared__ uint32_t wave_best[4];
     const int blk = blockIdx.x * kSuperBlocks + threadIdx.x;
     unsigned long long total = 0ull;
     const unsigned long long incl = scan256(blk < nblk ? block_cum[blk] : 0ull, wave_tot4, total);
-    if (blk < nblk) block_cum[blk] = incl;
+    if (blk < nblk) { block_cum[blk] = incl; store_coarse(coarse_cum, blockIdx.x, threadIdx.x, incl); }
     if (gridDim.x > 1) {
         if (threadIdx.x == 0) super_raw[blockIdx.x] = total;
         return;
@@ -582,7 +590,8 @@ __global__ __launch_bounds__(1024) void k_patch_supers(long long M, int nblk, in
                                                        const uint32_t* __restrict__ quarter_max,
                                                        const unsigned long long* __restrict__ touched_sum,
                                                        unsigned long long* __restrict__ block_cum,
-                                                       unsigned long long* __restrict__ super_new) {
+                                                       unsigned long long* __restrict__ super_new,
+                                                       unsigned long long* __restrict__ coarse_cum) {
     __shared__ unsigned long long wave_tot4[4];
     __shared__ uint32_t wave_best[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -650,7 +659,7 @@ __global__ __launch_bounds__(1024) void k_patch_supers(long long M, int nblk, in
     const unsigned long long incl = scan256(sum, wave_tot4, total);   // sum is 0 for tid >= 256
     if (tid < kSuperBlocks) {
         const int blk = blk0 + tid;
-        if (blk < nblk) block_cum[blk] = incl;
+        if (blk < nblk) { block_cum[blk] = incl; store_coarse(coarse_cum, s, tid, incl); }
         if (tid == 0) super_new[s] = total;
     }
 }
@@ -696,7 +705,8 @@ constexpr int kFusedSuperMin = 64;      // from this many super-blocks on, one w
 __global__ __launch_bounds__(1024) void k_update_small(
     float* __restrict__ weights, int M, const long long* __restrict__ idx, const float* __restrict__ prio,
     int K, float alpha, WsHeader* hdr, WsIndexState* ist, unsigned long long* __restrict__ block_cum, int nblk,
-    unsigned long long* __restrict__ super_cum, unsigned long long* __restrict__ sub_sum) {
+    unsigned long long* __restrict__ super_cum, unsigned long long* __restrict__ sub_sum,
+    unsigned long long* __restrict__ coarse_cum) {
     __shared__ unsigned long long sums[1024];
     __shared__ unsigned long long wave_tot[16];
     __shared__ uint32_t wave_max_bits[16];
@@ -767,7 +777,7 @@ __global__ __launch_bounds__(1024) void k_update_small(
     __syncthreads();
     unsigned long long before = 0ull, total = 0ull;
     for (int w = 0; w < 16; ++w) { if (w < wave) before += wave_tot[w]; total += wave_tot[w]; }
-    if (tid < nblk) block_cum[tid] = before + incl;
+    if (tid < nblk) { block_cum[tid] = before + incl; store_coarse(coarse_cum, 0, tid, before + incl); }
     if (tid < kSuperBlocks) super_cum[tid] = total;   // a single super-block
     if (tid == 0) {
         hdr->wmax_bits = wb;
@@ -792,10 +802,12 @@ __device__ __forceinline__ int group_count(bool pred, int group) {
 
 // Rank of t in the 256-entry run `run` (entries at index >= limit count as +inf), and the entry
 // just before that rank (0 for rank 0).  All 16 lanes of a group pass the same t.
-__device__ __forceinline__ int search256(const unsigned long long* __restrict__ run, int limit,
+// `coarse` holds run[15], run[31], .. contiguously.
+__device__ __forceinline__ int search256(const unsigned long long* __restrict__ run,
+                                         const unsigned long long* __restrict__ coarse, int limit,
                                          unsigned long long t, int group, int gl, unsigned long long& before) {
     const int ia = 16 * gl + 15;
-    const unsigned long long va = ia < limit ? run[ia] : ~0ull;
+    const unsigned long long va = ia < limit ? coarse[gl] : ~0ull;
     const int chunk = group_count(va <= t, group);                 // 0..16
     const int ib = 16 * min(chunk, 15) + gl;
     const unsigned long long vb = (chunk < 16 && ib < limit) ? run[ib] : ~0ull;
@@ -810,12 +822,17 @@ __global__ __launch_bounds__(256) void k_sample(
     const float* __restrict__ weights, long long M, const WsHeader* __restrict__ hdr,
     const unsigned long long* __restrict__ block_cum, int nblk,
     const unsigned long long* __restrict__ super_cum, const unsigned long long* __restrict__ sub_sum,
-    const double* __restrict__ uniforms, int K, long long* __restrict__ idx_out, float* __restrict__ prob_out,
+    const unsigned long long* __restrict__ coarse_cum, const double* __restrict__ uniforms, int K, long long* __restrict__ idx_out, float* __restrict__ prob_out,
     uint32_t* __restrict__ flags) {
     // The 256 super-block prefixes are the same for every draw: one load per thread brings them
     // into LDS, which takes the first level's two dependent probes off the global-memory path.
     __shared__ unsigned long long super_lds[kSuperBlocks];
-    super_lds[threadIdx.x] = super_cum[threadIdx.x];
+    __shared__ unsigned long long super_coarse[16];  // entries 15, 31, .. again, side by side (no bank conflicts)
+    {
+        const unsigned long long sc = super_cum[threadIdx.x];
+        super_lds[threadIdx.x] = sc;
+        if ((threadIdx.x & 15) == 15) super_coarse[threadIdx.x >> 4] = sc;
+    }
     __syncthreads();                                 // before any wave may leave
     const int lane = threadIdx.x & 63, group = lane >> 4, gl = lane & 15;
     const int wave_id = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
@@ -837,12 +854,13 @@ __global__ __launch_bounds__(256) void k_sample(
 
     // level 1: first super-block whose inclusive prefix exceeds t (the padding equals Total > t)
     unsigned long long before;
-    const int sblk = search256(super_lds, kSuperBlocks, t, group, gl, before);
+    const int sblk = search256(super_lds, super_coarse, kSuperBlocks, t, group, gl, before);
     bool stale = sblk >= kSuperBlocks;               // cannot happen with a current index
     unsigned long long rem = t - (stale ? 0ull : before);
     // level 2: first block of that super-block whose inclusive prefix exceeds the remainder
     const int first = (stale ? 0 : sblk) * kSuperBlocks;
-    const int within = search256(block_cum + first, nblk - first, rem, group, gl, before);
+    const int within = search256(block_cum + first, coarse_cum + (stale ? 0 : sblk) * 16, nblk - first, rem, group, gl,
+                                 before);
     stale = stale || within >= kSuperBlocks || first + within >= nblk;
     const int blk = stale ? 0 : first + within;
     rem -= stale ? 0ull : before;
@@ -877,7 +895,7 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
     if (M <= kSmallReplay && K <= kSmallBatch) {
         hipLaunchKernelGGL(k_update_small, dim3(1), dim3(1024), 0, st, weights, (int)M, idx, prio, K, alpha,
-                           w.hdr, w.ist, w.block_cum, nblk, w.super_cum, w.sub_sum);
+                           w.hdr, w.ist, w.block_cum, nblk, w.super_cum, w.sub_sum, w.coarse_cum);
         return hipGetLastError();
     }
     if (K > 0 && K <= kSmallBatch) {
@@ -890,16 +908,16 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     if (nsuper >= kFusedSuperMin) {
         const uint32_t* always = nullptr;
         hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, always);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, w.coarse_cum, always);
         hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, always);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, w.coarse_cum, always);
     } else {
         hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, nblk, w.hdr, w.partial_max,
                            w.chunk_max, (const uint32_t*)nullptr);
         hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M,
                            w.partial_max, w.block_cum, nblk, w.sub_sum);
         hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, w.block_cum, nblk, w.super_cum,
-                           w.partial_max, w.hdr, w.ist, M);
+                           w.partial_max, w.hdr, w.ist, M, w.coarse_cum);
         if (nsuper == 1) return hipGetLastError();   // the scan kernel finalised the index itself
     }
     hipLaunchKernelGGL(k_prefix_super, dim3(1), dim3(256), 0, st, w.super_cum, nsuper, w.partial_max, w.hdr, w.ist, M);
@@ -929,11 +947,11 @@ hipError_t insert_launch(float* weights, long long M, long long cursor, const fl
                            prio, K, alpha, slots_out, c0, w.hdr, w.quarter_max, w.touched_sum, w.sub_sum);
         hipLaunchKernelGGL(k_patch_supers, dim3((unsigned)ns), dim3(1024), 0, st, M, nblk, b0, nt, c0, nc, nchunk, s0,
                            nsuper, w.hdr, w.ist, w.partial_max, w.chunk_max, w.quarter_max, w.touched_sum,
-                           w.block_cum, w.super_new);
+                           w.block_cum, w.super_new, w.coarse_cum);
         hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, gate);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, w.coarse_cum, gate);
         hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)nsuper), dim3(1024), 0, st, weights, M, w.hdr,
-                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, gate);
+                           w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, w.coarse_cum, gate);
         hipLaunchKernelGGL(k_patch_finish, dim3(1), dim3(256), 0, st, w.super_cum, w.super_new, nsuper, s0, ns,
                            w.partial_max, w.hdr, w.ist, M);
         return hipGetLastError();
@@ -950,7 +968,7 @@ hipError_t sample_launch(const float* weights, long long M, const ReplayWs& w, c
     const long long waves = ((long long)K + 3) / 4;      // four draws per wave
     const unsigned g = (unsigned)((waves * kWave + 255) / 256);
     hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, w.hdr, w.block_cum, nblk, w.super_cum,
-                       w.sub_sum, uniforms, K, idx_out, prob_out, &w.hdr->flags);
+                       w.sub_sum, w.coarse_cum, uniforms, K, idx_out, prob_out, &w.hdr->flags);
     return hipGetLastError();
 }
 

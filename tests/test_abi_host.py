@@ -39,8 +39,8 @@ def test_error_codes_match_header():
 def test_workspace_bytes(L):
     assert b.workspace_bytes(0) == 256                       # status block only
     # status, super-block prefixes, partial maxima, new super-block totals, chunk and quarter-chunk
-    # maxima, block sums of a patched insert
-    fixed = 256 + 2048 + 4096 + 2048 + 16384 + 65536 + 67584
+    # maxima, block sums of a patched insert, every 16th block prefix again
+    fixed = 256 + 2048 + 4096 + 2048 + 16384 + 65536 + 67584 + 32768
     # per block of 256 weights: one u64 prefix and 16 u64 sub-block sums, each array rounded to 256 bytes
     assert b.workspace_bytes(1) == fixed + 256 + 256
     assert b.workspace_bytes(256 * 32) == fixed + 256 + 32 * 128
