@@ -173,10 +173,11 @@ def bench_replay(args, b, torch, synth, dev):
     elapsed, ms = _timed(torch, step, args.steps, args.warmup)
     st, rc = ws.status()
     assert rc == b.OK and st.flags == 0, f"status flags {st.flags:#x} rc {rc}"
-    # per step: one sweep of the weights (maxima and integer block sums together) and the index
-    # written once; per draw one 1 KB block of weights (the 4 KB of index entries it consults stay
-    # in cache) and 16 B of I/O; per update 12 B in and one 64-byte sector read-modify-written
-    alg_bytes = M * 4 + (M // 256) * 8 + K * (1024 + 8 + 8) + K * (8 + 4 + 64)
+    # per step: one sweep of the weights (maxima and integer sums together) and the index written
+    # once (a u64 per 16 weights and per 256 weights); per draw the 16 sub-block sums of one block,
+    # the 16 weights of one sub-block (the upper index levels it consults stay in cache) and 16 B
+    # of I/O; per update 12 B in and one 64-byte sector read-modify-written
+    alg_bytes = M * 4 + (M // 16) * 8 + (M // 256) * 8 + K * (128 + 64 + 8 + 8) + K * (8 + 4 + 64)
     cpu = None
     if not args.no_cpu_baseline:
         import oracle

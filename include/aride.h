@@ -88,6 +88,8 @@ typedef struct {
 /*
  * Bytes of device workspace needed for a replay buffer of capacity M (pass M = 0 when
  * only the scoring calls are used: the workspace then holds just the status block).
+ * With a replay index it is about 190 KB plus 0.53 * M bytes (an integer sum per 16 weights
+ * and per 256 weights): 8.6 MB beside the 64 MB of weights at M = 2^24.
  * Host-only; *out_bytes is a host pointer.  The workspace must be 256-byte aligned.
  */
 int aride_workspace_bytes(int64_t M, size_t* out_bytes);
