@@ -266,8 +266,9 @@ def bench_insert(args, b, torch, synth, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps first; the first few dozen launches after start-up run a little slower")
     ap.add_argument("--config", type=int, default=1, help="workload index (1 = learner batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the CPU sample")
