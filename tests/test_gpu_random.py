@@ -144,3 +144,55 @@ def test_replay_random_buffers(oracle):
         torch.cuda.synchronize()
         oi, _, _ = oracle.sample_prioritized(npf(w), npf(u))
         np.testing.assert_array_equal(npf(got), oi, err_msg=f"case {case} after insert")
+
+
+def test_large_buffer_random_inserts_and_updates(oracle):
+    # the patched-insert and one-sweep-rebuild routes on a buffer of 65+ super-blocks: random
+    # cursors, batch lengths and magnitudes, so that the exponent of the maximum moves both ways
+    rng = np.random.default_rng(13 + SEED)
+    M = int(rng.choice([64 * 65536 + 3 * 256 + 9, 80 * 65536, 70 * 65536 + 1]))
+    p = np.exp(rng.standard_normal(M) * 1.5).astype(np.float32)
+    w_host = np.zeros(M, np.float32)
+    oracle.update_priorities(w_host, np.arange(M), p, 0.6)
+    w = torch.as_tensor(w_host, device=DEV)
+    ws = b.Workspace(M)
+    b.update_priorities(w, None, None, 0.6, ws)
+    cursor = int(rng.integers(0, M))
+    for step in range(14):
+        kind = rng.choice(["insert", "insert", "insert", "update"])
+        scale = float(rng.choice([1e-4, 1e-2, 1.0, 1.0, 30.0, 1e4]))
+        if kind == "insert":
+            K = int(rng.choice([1, 17, 255, 4096, 4097, 70000, M // 8, M // 8 + 1, M // 3]))
+            if rng.random() < 0.3:
+                cursor = int(rng.choice([0, M - 1, M - K // 2 - 1, 65536 * 7 - 3]))
+            print(f"step {step}: insert K={K} at {cursor} scale {scale}", flush=True)
+            prio = torch.as_tensor((rng.random(K) * scale).astype(np.float32), device=DEV)
+            wo = npf(w).copy()
+            nc = b.replay_insert(w, cursor, prio, 0.6, ws)
+            oc, _ = oracle.replay_insert(wo, cursor, npf(prio), 0.6)
+            torch.cuda.synchronize()
+            assert nc == oc
+            np.testing.assert_allclose(npf(w), wo, rtol=1e-6)
+            cursor = nc
+        else:
+            K = int(rng.choice([0, 3, 9000, 70000]))
+            print(f"step {step}: update K={K} scale {scale}", flush=True)
+            idx = torch.as_tensor(rng.integers(0, M, K), device=DEV)
+            prio = torch.as_tensor((rng.random(K) * scale).astype(np.float32), device=DEV)
+            wo = npf(w).copy()
+            b.update_priorities(w, idx if K else None, prio if K else None, 0.6, ws)
+            torch.cuda.synchronize()
+            oracle.update_priorities(wo, npf(idx), npf(prio), 0.6)
+            np.testing.assert_allclose(npf(w), wo, rtol=1e-6)
+        u = synth.uniforms(500, 6000 + step + 100 * SEED, DEV)
+        got = torch.empty(500, dtype=torch.int64, device=DEV)
+        prob = torch.empty(500, device=DEV)
+        b.sample_prioritized(w, u, ws, got, prob)
+        torch.cuda.synchronize()
+        wh = npf(w)
+        oi, op, _ = oracle.sample_prioritized(wh, npf(u))
+        np.testing.assert_array_equal(npf(got), oi, err_msg=f"step {step}")
+        np.testing.assert_allclose(npf(prob), op.astype(np.float32), rtol=1e-6)
+        st, rc = ws.status()
+        _, total = oracle.quantise_weights(wh)
+        assert rc == b.OK and st.total == total, f"step {step}"
