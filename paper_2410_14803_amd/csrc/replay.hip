@@ -323,6 +323,21 @@ __device__ __forceinline__ unsigned long long quantise_capped(float w, int e) {
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// ... and for a weight known to be valid and below 2^e (see k_super_sums): nothing to test or cap.
+__device__ __forceinline__ unsigned long long quantise_plain(float w, int e) {
+    const float x = ldexpf(w, 39 - e);
+    const uint32_t hi = (uint32_t)(x * 2.3283064365386963e-10f);
+    const uint32_t lo = (uint32_t)fmaf(-(float)hi, 4294967296.f, x);
+    return ((unsigned long long)hi << 32) | lo;
+}
+// Bit pattern of the float 2^e (0 when 2^e is below the smallest subnormal, +inf's when above the largest).
+__device__ __forceinline__ uint32_t pow2_bits(int e) {
+    if (e > 127) return 0x7F800000u;
+    if (e >= -126) return (uint32_t)(e + 127) << 23;
+    if (e >= -149) return 1u << (e + 149);
+    return 0u;
+}
+
 // The sweep of large buffers: one workgroup of 1024 threads per super-block (65536 weights);
 // each wave sums 16 blocks of 256 weights as integers, then the 256 block sums are scanned in
 // LDS.  Writes the within-super-block inclusive prefixes and the super-block's total.
@@ -367,29 +382,14 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
 #pragma unroll
         for (int j = 0; j < 16; ++j) v[j] = load_block_quad(weights, M, blk_first + j, lane);
     }
+    // SPEC: a weight whose bit pattern is below `safe` is valid (non-negative, finite) and below
+    // 2^e, so it needs neither the validity test nor the cap; whole batches of such weights --
+    // practically all of them -- are quantised by the short form.  The maxima are taken batch by
+    // batch as well, so that nothing waits for the last load before the first is used.
+    uint32_t raw = 0u, safe = 0u;
     if constexpr (SPEC) {
         e = hdr->exponent;
-        // this wave's 16 blocks are chunk 16*sblk + wave (see k_weight_max for the two paths)
-        uint32_t raw = 0u, best = 0u;
-        bool bad = false;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            raw = max(max(raw, float_to_bits(v[j].x)), float_to_bits(v[j].y));
-            raw = max(max(raw, float_to_bits(v[j].z)), float_to_bits(v[j].w));
-        }
-        if (raw < 0x7F800000u) {
-            best = raw;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) best = max(best, quad_max_bits(v[j], bad));
-        }
-        best = wave_max_u32(best);
-        const bool any_bad = __any(bad);
-        if (lane == 0) {
-            chunk_max[sblk * 16 + wave] = best;
-            wave_best[wave] = best;                    // read after the barrier below
-            if (any_bad) atomicOr(&hdr->flags, 0x2u);
-        }
+        safe = min(0x7F800000u, pow2_bits(e));
         // partial_max entries past the last super-block must not keep an older, larger buffer's maxima
         if (sblk == 0) for (int i = 4 * (int)gridDim.x + tid; i < kMaxParts; i += 1024) partial_max[i] = 0u;
     }
@@ -398,14 +398,31 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         unsigned long long part[4];
+        bool plain = false;
+        if constexpr (SPEC) {
+            uint32_t rb = 0u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float4 w = v[4 * g + j];
+                rb = max(max(rb, float_to_bits(w.x)), float_to_bits(w.y));
+                rb = max(max(rb, float_to_bits(w.z)), float_to_bits(w.w));
+            }
+            raw = max(raw, rb);
+            plain = __all(rb < safe);                      // wave-uniform
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float4 w = v[4 * g + j];
-            if constexpr (SPEC)
-                part[j] = quantise_capped(w.x, e) + quantise_capped(w.y, e) + quantise_capped(w.z, e) +
-                          quantise_capped(w.w, e);
-            else
+            if constexpr (SPEC) {
+                if (plain)
+                    part[j] = quantise_plain(w.x, e) + quantise_plain(w.y, e) + quantise_plain(w.z, e) +
+                              quantise_plain(w.w, e);
+                else
+                    part[j] = quantise_capped(w.x, e) + quantise_capped(w.y, e) + quantise_capped(w.z, e) +
+                              quantise_capped(w.w, e);
+            } else {
                 part[j] = quantise(w.x, e) + quantise(w.y, e) + quantise(w.z, e) + quantise(w.w, e);
+            }
             part[j] = quad_sum_u64(part[j]);
         }
         {   // one store for the four blocks: lane 4i + r writes sub-block i of block 4g + r
@@ -416,6 +433,24 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
         }
         const unsigned long long sum = transposed_sum4<true>(part, lane);
         if ((lane & 15) == 0) sums[wave * 16 + 4 * g + (lane >> 4)] = sum;
+    }
+    if constexpr (SPEC) {
+        // this wave's 16 blocks are chunk 16*sblk + wave (see k_weight_max for the two paths)
+        uint32_t best = 0u;
+        bool bad = false;
+        if (raw < 0x7F800000u) {
+            best = raw;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) best = max(best, quad_max_bits(v[j], bad));
+        }
+        best = wave_max_u32(best);
+        const bool any_bad = __any(bad);
+        if (lane == 0) {
+            chunk_max[sblk * 16 + wave] = best;
+            wave_best[wave] = best;
+            if (any_bad) atomicOr(&hdr->flags, 0x2u);
+        }
     }
     __syncthreads();
     if constexpr (SPEC) {
