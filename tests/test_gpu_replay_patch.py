@@ -204,3 +204,16 @@ def test_patch_interleaved_with_updates_and_an_infinite_priority(oracle):
     torch.cuda.synchronize()
     oi, _, _ = oracle.sample_prioritized(npf(w), npf(u))
     np.testing.assert_array_equal(npf(idx), oi)
+
+
+def test_patch_at_maximum_capacity(oracle):
+    # M = ARIDE_MAX_REPLAY: 256 super-blocks, 4096 chunks, every fixed-size array of the workspace full
+    M = b.MAX_REPLAY
+    w, ws = start(oracle, M, 16)
+    rng = np.random.default_rng(3)
+    cursor = M - 40_000
+    for it, K in enumerate((65_536, 1, M // 8)):
+        prio = (rng.random(K) * 0.5).astype(np.float32)
+        cursor = insert(oracle, w, ws, cursor, prio, slots=(K < 100_000))
+        check(oracle, w, ws, 90 + it, f"max capacity K={K}", n=800)
+    assert cursor == (M - 40_000 + 65_536 + 1 + M // 8) % M
