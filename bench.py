@@ -433,6 +433,15 @@ def main():
                                "kind": "oracle", "seconds": tc1 - tc0,
                                "sample": f"first {nb} trajectories of the batch ({n_s} steps, {r_s} logit rows), "
                                          f"whole path incl. one {K}-draw sample and update on the {M}-entry buffer"}
+        # the same oracle on one thread, on a share of those rows that takes about as long (the logit
+        # reduction is all but the whole cost)
+        r1 = max(cfg.A, (r_s // threads) // cfg.A * cfg.A)
+        ts0 = time.perf_counter()
+        oracle.score_logits(lb[:r1], tk[:r1], cfg.A, nthreads=1)
+        ts1 = time.perf_counter()
+        out["cpu_baseline"]["single_thread"] = {"value": (r1 // cfg.A) / (ts1 - ts0), "unit": "trajectory-steps/s",
+                                                "cores": 1, "seconds": ts1 - ts0,
+                                                "sample": f"logit reduction of the first {r1} rows"}
     print(json.dumps(out), flush=True)
 
 
