@@ -97,11 +97,17 @@ def _p(t, dtype=None):
     assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
     if dtype is not None:
         assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
-    return ctypes.c_void_p(t.data_ptr())
+    return t.data_ptr()
+
+
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
 
 
 def _stream():
-    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    """Handle of torch's current stream on the current device (what every call is enqueued on)."""
+    if _raw_stream is not None:        # the short way to the same handle: a third of the cost of the call below
+        return _raw_stream(torch.cuda.current_device())
+    return torch.cuda.current_stream().cuda_stream
 
 
 def _check(fn, rc):
