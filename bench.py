@@ -104,6 +104,8 @@ def _timed(torch, fn, steps, warmup):
 def bench_retrace(args, b, torch, synth, dev):
     """One step = retrace_targets + compute_priorities over the long-scan batch (config 3)."""
     cfg = synth.CONFIGS[3]
+    if args.batch_scale != 1:                 # the same length mix, more trajectories
+        cfg = synth.scaled(cfg, B=cfg.B * args.batch_scale)
     seed = synth.BASE_SEED + cfg.index
     off_np = synth.trajectory_offsets(cfg, seed)
     N = int(off_np[-1])
@@ -280,6 +282,9 @@ def main():
                          "insert: circular insert of 65 536 entries into that buffer, index patched")
     ap.add_argument("--rebuild-every-insert", action="store_true",
                     help="with --path insert: follow every insert by a full index rebuild (the comparison)")
+    ap.add_argument("--batch-scale", type=int, default=1,
+                    help="with --path retrace: multiply the number of trajectories (the kernels are "
+                         "launch-bound at the configured size)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()
