@@ -217,3 +217,24 @@ def test_patch_at_maximum_capacity(oracle):
         cursor = insert(oracle, w, ws, cursor, prio, slots=(K < 100_000))
         check(oracle, w, ws, 90 + it, f"max capacity K={K}", n=800)
     assert cursor == (M - 40_000 + 65_536 + 1 + M // 8) % M
+
+
+@pytest.mark.parametrize("top", [3.0e38, 1.0, 2.0 ** -126, 1.0e-41, 1.4e-45])
+def test_large_buffer_extreme_magnitudes(oracle, top):
+    # weights written directly (then a rebuild with K = 0): the largest finite values, the smallest
+    # normal, subnormals down to the last one -- the exponent of the maximum runs over its whole range
+    M = M_BIG
+    rng = np.random.default_rng(int(-np.log2(top)) + 200)
+    w_host = (rng.random(M) * top).astype(np.float32)
+    w_host[rng.random(M) < 0.5] = 0.0
+    w_host[12345] = np.float32(top)
+    w = torch.as_tensor(w_host, device=DEV)
+    ws = b.Workspace(M)
+    b.update_priorities(w, None, None, 1.0, ws)
+    b.update_priorities(w, None, None, 1.0, ws)     # again: now the standing exponent is the right guess
+    st = check(oracle, w, ws, 300, f"top={top}")
+    assert st.exponent == int(np.floor(np.log2(float(np.float32(top))))) + 1
+    # a patched insert of entries of the same magnitude (alpha = 1 stores the priorities as they are)
+    prio = (rng.random(5000) * top * 0.5).astype(np.float32)
+    insert(oracle, w, ws, M - 2000, prio, alpha=1.0)
+    check(oracle, w, ws, 301, f"top={top} after insert")
