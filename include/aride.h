@@ -213,8 +213,8 @@ int aride_compute_priorities(const float* td, const float* rho, const float* ent
  *     for k = 0..K-1 in order:  weights[idx[k]] = (float) pow(max(prio[k], 0), alpha)
  * so a repeated index keeps its LAST occurrence; NaN priorities store 0; indices
  * outside [0, M) are skipped and set ARIDE_ST_BAD_INDEX.  The sampling index in the
- * workspace (integer block sums of the quantised weights and their prefix) is then
- * rebuilt from the whole buffer.  K == 0 rebuilds only: call it that way after
+ * workspace (integer sums of the quantised weights per 16 and per 256 weights, and the
+ * prefixes of the latter) is then rebuilt from the whole buffer.  K == 0 rebuilds only: call it that way after
  * writing `weights` directly.
  *
  *  weights fp32 [M] in/out, 16-byte aligned, 1 <= M <= ARIDE_MAX_REPLAY;
@@ -253,7 +253,7 @@ int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* 
  *     prob_out[k] = (float)(q_idx / Total)
  * NaN/negative/infinite weights carry no mass.  Zero-weight entries are never drawn.
  * Sampling is with replacement; u < 0 or NaN is read as 0 (ARIDE_ST_BAD_UNIFORM).
- * Requires the index built by the last aride_update_priorities on the same
+ * Requires the index left by the last aride_update_priorities or aride_replay_insert on the same
  * `weights` and workspace (only the status word of the workspace is written).  If the
  * buffer has no mass every idx_out[k] = -1.
  *
