@@ -116,8 +116,7 @@ __global__ __launch_bounds__(256) void k_insert(float* __restrict__ weights, lon
     if (slots_out) slots_out[k] = slot;
 }
 
-// Largest valid weight of the 256 weights of block `blk` (bit pattern; 0 when there is none),
-// reduced over the wave; `bad` collects negative, infinite or NaN entries (-0 is fine).
+// This lane's four weights (lane * 4 ..) of block `blk`; entries past the end of the buffer read 0.
 __device__ __forceinline__ float4 load_block_quad(const float* __restrict__ weights, long long M, int blk, int lane) {
     const long long base = (long long)blk * kReplayBlock + lane * 4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -129,6 +128,8 @@ __device__ __forceinline__ float4 load_block_quad(const float* __restrict__ weig
     }
     return v;
 }
+// Largest valid weight among four (bit pattern; 0 when there is none); `bad` collects negative,
+// infinite or NaN entries (-0 is fine).
 __device__ __forceinline__ uint32_t quad_max_bits(const float4& v, bool& bad) {
     uint32_t best = 0u;
     auto see = [&](float w) {
@@ -150,16 +151,15 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 // one wave reduction -- and stores its maximum to chunk_max; the maximum of the workgroup's four
 // chunks goes to partial_max[g], and the consumers reduce those 1024 words themselves.  (One
 // atomic per wave onto a single header word was measured at ~160 us for M = 2^24: same-address
-// atomics serialise.)  With a gate, the kernel runs only when *gate is nonzero.
+// atomics serialise.)  Used for buffers below 64 super-blocks; larger ones find their maxima
+// in the sweep that sums them (k_super_sums).
 static_assert(kMaxChunks == 4 * kMaxParts, "one chunk per wave of the maximum pass");
 static_assert((long long)kMaxChunks * kChunkBlocks * kReplayBlock >= (1 << 24), "chunks cover the largest buffer");
 
 __global__ __launch_bounds__(256) void k_weight_max(const float* __restrict__ weights, long long M, int nblk,
                                                     WsHeader* hdr, uint32_t* __restrict__ partial_max,
-                                                    uint32_t* __restrict__ chunk_max,
-                                                    const uint32_t* __restrict__ gate) {
+                                                    uint32_t* __restrict__ chunk_max) {
     __shared__ uint32_t wave_best[4];
-    if (gate && *gate == 0u) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = 4 * blockIdx.x + wave;
     const int first = chunk * kChunkBlocks;
@@ -948,7 +948,7 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
                            w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, w.coarse_cum, always);
     } else {
         hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, nblk, w.hdr, w.partial_max,
-                           w.chunk_max, (const uint32_t*)nullptr);
+                           w.chunk_max);
         hipLaunchKernelGGL(k_block_sums, dim3((unsigned)((nblk + 3) / 4)), dim3(256), 0, st, weights, M,
                            w.partial_max, w.block_cum, nblk, w.sub_sum);
         hipLaunchKernelGGL(k_scan_supers, dim3((unsigned)nsuper), dim3(256), 0, st, w.block_cum, nblk, w.super_cum,
