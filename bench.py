@@ -31,6 +31,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # digits of its sha256) and for the learner-batch workload; reported as null otherwise.
 TRAFFIC = {"source_sha256": "53ae0bff741e2a75", "config": 1, "logit_rows": 82144,
            "bytes_per_launch": 5282315764}
+# The same for the gradient sweep (profiles/k_actor_grad_learner_batch.md), scaled by the factors the copy gave.
+TRAFFIC_ACTOR = {"source_sha256": "ae2247054849a908", "config": 1, "logit_rows": 82144,
+                 "bytes_per_launch": 10564834816}
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 
@@ -82,9 +85,17 @@ def bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, ste
         "config": {"workload": f"{cfg.name} (config {cfg.index}), actor_grad path", "traj_steps": N,
                    "logit_rows": R, "vocab": cfg.V, "grad_dtype": "bf16"},
         "roofline": {"bound": "hbm", "kernel": "k_actor_grad (+ k_actor_loss)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": _actor_traffic(args, R),
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
         "cpu_baseline": cpu}), flush=True)
+
+
+def _actor_traffic(args, R):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2410_14803_amd", "csrc", "actor_grad.hip")
+    same = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == TRAFFIC_ACTOR["source_sha256"]
+    ok = same and args.config == TRAFFIC_ACTOR["config"] and R == TRAFFIC_ACTOR["logit_rows"]
+    return TRAFFIC_ACTOR["bytes_per_launch"] if ok else None
 
 
 def _timed(torch, fn, steps, warmup):
