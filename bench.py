@@ -293,6 +293,9 @@ def main():
                          "insert: circular insert of 65 536 entries into that buffer, index patched")
     ap.add_argument("--rebuild-every-insert", action="store_true",
                     help="with --path insert: follow every insert by a full index rebuild (the comparison)")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="number of copies of the logits swept in turn (0: as many as make 512 MB, i.e. 1 for "
+                         "the learner batch and 4 for the tiny one)")
     ap.add_argument("--batch-scale", type=int, default=1,
                     help="with --path retrace: multiply the number of trajectories (the kernels are "
                          "launch-bound at the configured size)")
@@ -326,6 +329,10 @@ def main():
     off = torch.as_tensor(off_np, device=dev)
     logits = synth.logits_bf16(R, cfg.V, seed + 1, dev, heavy_tail=cfg.heavy_tail)
     tokens = synth.action_tokens(logits, seed + 2)
+    # A batch that fits the 256 MB last-level cache is swept from several copies in turn (at least
+    # 512 MB together), so that what is timed is HBM and not the cache; the learner batch is 5 GB.
+    copies = args.rotate if args.rotate > 0 else max(1, -(-(512 << 20) // (R * cfg.V * 2)))
+    logits_ring = [logits] + [logits.clone() for _ in range(copies - 1)]
     si = synth.step_inputs(cfg, off_np, seed + 4, dev)
     ws = b.Workspace(M, device=dev)
     f = lambda n: torch.empty(n, device=dev)
@@ -351,7 +358,7 @@ def main():
         return bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, step_logp, step_ent, si, N, R)
 
     def one_step(i, ev=None):
-        b.score_logits(logits, tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
+        b.score_logits(logits_ring[i % copies], tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
                        step_logp=step_logp, step_ent=step_ent, sweep_events=ev)
         b.retrace_targets(step_logp, logmu, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"],
                           target=target, td=td, rho=rho)
@@ -413,7 +420,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": B, "traj_steps": N,
                    "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
-                   "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha},
+                   "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha,
+                   "logit_copies_in_rotation": copies},
         "roofline": {"bound": "hbm", "kernel": "k_score_rows", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
