@@ -36,6 +36,9 @@ namespace aride {
 #ifndef ARIDE_SCORE_NT
 #define ARIDE_SCORE_NT 1        // 1: non-temporal loads
 #endif
+#ifndef ARIDE_SCORE_XCD_CHUNK
+#define ARIDE_SCORE_XCD_CHUNK 0 // consecutive workgroups' worth of rows per XCD and turn; 0: one eighth of all rows
+#endif
 
 constexpr long long kSplitMaxRows = 4096;   // up to this many rows (4 waves per SIMD) a row is split over 4 waves
 constexpr int kSplitMinVocab = 8192;        // ... provided each wave still gets a few KB of it
@@ -142,7 +145,18 @@ __global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
     const int lane = threadIdx.x & 63;
-    const long long row = (long long)blockIdx.x * ARIDE_SCORE_WAVES + (threadIdx.x >> 6);
+    // Workgroups are handed to the chip's 8 XCDs in turn (blockIdx mod 8).  The grid is a multiple
+    // of 8, and XCD x takes the x-th eighth of the rows (ARIDE_SCORE_XCD_CHUNK == 0) or, in
+    // every run of 8*CHUNK workgroups, the x-th run of CHUNK: each XCD, with its own L2 and its
+    // own paths to memory, then streams one contiguous region instead of every eighth 256 KB.
+    const long long per_xcd = gridDim.x >> 3, slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+#if ARIDE_SCORE_XCD_CHUNK == 0
+    const long long vblock = xcd * per_xcd + slot;
+#else
+    const long long vblock = (slot / ARIDE_SCORE_XCD_CHUNK) * (8 * ARIDE_SCORE_XCD_CHUNK) +
+                             xcd * ARIDE_SCORE_XCD_CHUNK + slot % ARIDE_SCORE_XCD_CHUNK;
+#endif
+    const long long row = vblock * ARIDE_SCORE_WAVES + (threadIdx.x >> 6);
     if (row >= R) return;   // whole waves leave together; the kernel has no workgroup barrier
 
     const int tok = tokens[row];
@@ -331,7 +345,12 @@ hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long 
             hipLaunchKernelGGL((k_score_rows_split<ARIDE_SCORE_UNROLL>), dim3((unsigned)R), dim3(256), 0, st, logits,
                                R, V, stride, tokens, tok_logp, tok_ent, status);
     } else {
-        const long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
+        long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
+#if ARIDE_SCORE_XCD_CHUNK == 0
+        blocks = (blocks + 7) / 8 * 8;                       // the kernel's row mapping wants a multiple of 8
+#else
+        blocks = (blocks + 8 * ARIDE_SCORE_XCD_CHUNK - 1) / (8 * ARIDE_SCORE_XCD_CHUNK) * (8 * ARIDE_SCORE_XCD_CHUNK);
+#endif
         if (timed)
             hipExtLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
                                   dim3(64 * ARIDE_SCORE_WAVES), 0, st, sweep_start, sweep_stop, 0, logits, R, V,
