@@ -100,6 +100,15 @@ __device__ __forceinline__ uint32_t float_to_bits(float f) { return __float_as_u
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Workgroups are handed to the chip's 8 XCDs in turn (blockIdx mod 8).  For a grid that is a
+// multiple of 8 this is the workgroup number under which XCD x works through the x-th eighth
+// of the grid, so that each XCD -- its own L2, its own paths to memory -- streams one contiguous
+// region of a tensor that the grid walks front to back.
+__device__ __forceinline__ long long xcd_contiguous_block() {
+    return (long long)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+}
+inline unsigned round_up_8(unsigned blocks) { return (blocks + 7u) / 8u * 8u; }
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, kWave));

@@ -367,7 +367,7 @@ __global__ __launch_bounds__(1024) void k_super_sums(const float* __restrict__ w
     // the grid is the number of super-blocks rounded up to a multiple of 8: workgroups go to the
     // chip's 8 XCDs in turn, and XCD x takes the x-th eighth of the super-blocks, one contiguous region
     const int nsuper = (nblk + kSuperBlocks - 1) / kSuperBlocks;
-    const int sblk = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
+    const int sblk = (int)xcd_contiguous_block();
     if (sblk >= nsuper) return;                    // the whole workgroup leaves
     int e = 0;
     if constexpr (!SPEC) {   // decided before any weight is read: this is usually all the kernel does
@@ -946,9 +946,9 @@ hipError_t update_launch(float* weights, long long M, const long long* idx, cons
     }
     if (nsuper >= kFusedSuperMin) {
         const uint32_t* always = nullptr;
-        hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)((nsuper + 7) / 8 * 8)), dim3(1024), 0, st, weights, M, w.hdr,
+        hipLaunchKernelGGL((k_super_sums<true>), dim3(round_up_8((unsigned)nsuper)), dim3(1024), 0, st, weights, M, w.hdr,
                            w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, w.coarse_cum, always);
-        hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)((nsuper + 7) / 8 * 8)), dim3(1024), 0, st, weights, M, w.hdr,
+        hipLaunchKernelGGL((k_super_sums<false>), dim3(round_up_8((unsigned)nsuper)), dim3(1024), 0, st, weights, M, w.hdr,
                            w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_cum, w.sub_sum, w.coarse_cum, always);
     } else {
         hipLaunchKernelGGL(k_weight_max, dim3(kMaxParts), dim3(256), 0, st, weights, M, nblk, w.hdr, w.partial_max,
@@ -987,9 +987,9 @@ hipError_t insert_launch(float* weights, long long M, long long cursor, const fl
         hipLaunchKernelGGL(k_patch_supers, dim3((unsigned)ns), dim3(1024), 0, st, M, nblk, b0, nt, c0, nc, nchunk, s0,
                            nsuper, w.hdr, w.ist, w.partial_max, w.chunk_max, w.quarter_max, w.touched_sum,
                            w.block_cum, w.super_new, w.coarse_cum);
-        hipLaunchKernelGGL((k_super_sums<true>), dim3((unsigned)((nsuper + 7) / 8 * 8)), dim3(1024), 0, st, weights, M, w.hdr,
+        hipLaunchKernelGGL((k_super_sums<true>), dim3(round_up_8((unsigned)nsuper)), dim3(1024), 0, st, weights, M, w.hdr,
                            w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, w.coarse_cum, gate);
-        hipLaunchKernelGGL((k_super_sums<false>), dim3((unsigned)((nsuper + 7) / 8 * 8)), dim3(1024), 0, st, weights, M, w.hdr,
+        hipLaunchKernelGGL((k_super_sums<false>), dim3(round_up_8((unsigned)nsuper)), dim3(1024), 0, st, weights, M, w.hdr,
                            w.partial_max, w.chunk_max, w.block_cum, nblk, w.super_new, w.sub_sum, w.coarse_cum, gate);
         hipLaunchKernelGGL(k_patch_finish, dim3(1), dim3(256), 0, st, w.super_cum, w.super_new, nsuper, s0, ns,
                            w.partial_max, w.hdr, w.ist, M);
