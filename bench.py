@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
 # plain 1 GiB copy kernel.  Valid only for the kernel source it was measured on (first 16 hex
 # digits of its sha256) and for the learner-batch workload; reported as null otherwise.
-TRAFFIC = {"source_sha256": "0196f66c024b236c", "config": 1, "logit_rows": 82144,
-           "bytes_per_launch": 5279301024}
+TRAFFIC = {"source_sha256": "742b3f85550ebb93", "config": 1, "logit_rows": 82144,
+           "bytes_per_launch": 5287430885}
 # The same for the gradient sweep (profiles/k_actor_grad_learner_batch.md), scaled by the factors the copy gave.
 TRAFFIC_ACTOR = {"source_sha256": "ae2247054849a908", "config": 1, "logit_rows": 82144,
                  "bytes_per_launch": 10564834816}
@@ -422,7 +422,7 @@ def main():
                    "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
                    "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha,
                    "logit_copies_in_rotation": copies},
-        "roofline": {"bound": "hbm", "kernel": "k_score_rows", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "k_score_rows_split (8 waves per row at this row length)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
     }

@@ -40,8 +40,8 @@ namespace aride {
 #define ARIDE_SCORE_XCD_CHUNK 0 // consecutive workgroups' worth of rows per XCD and turn; 0: one eighth of all rows
 #endif
 
-constexpr long long kSplitMaxRows = 4096;   // up to this many rows (4 waves per SIMD) a row is split over 4 waves
-constexpr int kSplitMinVocab = 8192;        // ... provided each wave still gets a few KB of it
+// 16-byte vectors per row from which a row is shared by 4, 8, 16 waves (16 KB, 48 KB, 192 KB rows)
+constexpr int kSplit4MinVec = 1024, kSplit8MinVec = 3072, kSplit16MinVec = 12288;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -217,19 +217,21 @@ __global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
     }
 }
 
-// The same sweep for batches of few rows, where one wave per row would leave most of the chip's
-// wave slots empty and the rows unevenly spread (2560 rows are 2.5 waves per SIMD): a workgroup
-// of four waves per row, each wave reducing a contiguous quarter of the row's 16-byte vectors
-// (wave 0 also takes the unaligned head and tail); the four (max, s, t) states meet in LDS
-// and are merged exactly as the 64 lane states are.
-template <int UNROLL>
-__global__ __launch_bounds__(256) void k_score_rows_split(
+// The sweep for long rows: one workgroup of WPR waves per row, each wave reducing a contiguous
+// share of the row's 16-byte vectors (wave 0 also takes the unaligned head and tail); the WPR
+// (max, s, t) states meet in LDS and are merged exactly as the 64 lane states are.  Fewer rows
+// are open at a time on each XCD than with one wave per row (2.5 % faster on 64 KB rows, 4 % on
+// 304 KB rows), and a batch of few rows still fills the chip (2560 rows would otherwise be 2.5
+// waves per SIMD).
+template <int UNROLL, int WPR>
+__global__ __launch_bounds__(64 * WPR) void k_score_rows_split(
     const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
-    __shared__ float part[4][3];
+    __shared__ float part[WPR][3];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long row = blockIdx.x;            // grid = R workgroups
+    const long long row = xcd_contiguous_block();   // the grid is R rounded up to a multiple of 8
+    if (row >= R) return;                           // the whole workgroup leaves
 
     const int tok = tokens[row];
     const bool live = tok >= 0 && tok < V;
@@ -245,10 +247,10 @@ __global__ __launch_bounds__(256) void k_score_rows_split(
         const int nvec = (V - head) >> 3;
         const int tail0 = head + (nvec << 3);
         const u32x4* pv = reinterpret_cast<const u32x4*>(p + head);
-        const int quarter = (((nvec + 3) >> 2) + kWave - 1) & ~(kWave - 1);   // whole 1 KB pieces per wave
-        const int end = min(nvec, (wave + 1) * quarter);
+        const int share = (((nvec + WPR - 1) / WPR) + kWave - 1) & ~(kWave - 1);   // whole 1 KB pieces per wave
+        const int end = min(nvec, (wave + 1) * share);
 
-        int i = wave * quarter + lane;
+        int i = wave * share + lane;
         for (; i + (UNROLL - 1) * kWave < end; i += UNROLL * kWave) {
             u32x4 v[UNROLL];
 #pragma unroll
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(256) void k_score_rows_split(
             }
         }
     }
-    // this wave's quarter: common reference = its exact maximum
+    // this wave's share: common reference = its exact maximum
     const float Mw = wave_max(a.mx);
     float s, t;
     to_common(a.negk, a.s0 + a.s1, a.t0 + a.t1, Mw * kLog2e, s, t);
@@ -283,11 +285,13 @@ __global__ __launch_bounds__(256) void k_score_rows_split(
     if (threadIdx.x == 0) {
         float lp = 0.f, en = 0.f;
         if (live) {
-            const float M = fmaxf(fmaxf(part[0][0], part[1][0]), fmaxf(part[2][0], part[3][0]));
+            float M = part[0][0];
+#pragma unroll
+            for (int w = 1; w < WPR; ++w) M = fmaxf(M, part[w][0]);
             const float kc = M * kLog2e;
             float S = 0.f, T = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
+            for (int w = 0; w < WPR; ++w) {
                 float sw, tw;
                 to_common(-(part[w][0] * kLog2e), part[w][1], part[w][2], kc, sw, tw);
                 S += sw; T += tw;
@@ -328,37 +332,46 @@ __global__ __launch_bounds__(256) void k_step_sums(
     }
 }
 
+// A sweep kernel goes out with the two events attached to its own dispatch, or plainly.
+template <typename... Args, typename F = void (*)(Args...)>
+static void launch_sweep(F kernel, dim3 grid, dim3 block, hipStream_t st, hipEvent_t start, hipEvent_t stop,
+                         Args... args) {
+    if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, start, stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+}
+
 // Row sweep, then (when a per-step output is wanted) the per-step sums of the per-token arrays.
 // With events, they are attached to the dispatch of the row sweep itself: the time between
 // them is that kernel's execution time, with no marker packets on the stream around it.
+// Long rows are shared by 4, 8 or 16 waves so that each wave gets 6 to 16 KB of the row
+// (measured on 64 KB and 304 KB rows: 8 and 16 waves are the fastest there; a wave left with
+// 4 KB is much slower); rows below 16 KB take the one-wave-per-row kernel.
 hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long long stride,
                                const int* tokens, int A, float* tok_logp, float* tok_ent,
                                float* step_logp, float* step_ent, uint32_t* status, hipStream_t st,
                                hipEvent_t sweep_start, hipEvent_t sweep_stop) {
-    const bool timed = sweep_start || sweep_stop;
-    if (R <= kSplitMaxRows && V >= kSplitMinVocab) {      // few long rows: four waves per row
-        if (timed)
-            hipExtLaunchKernelGGL((k_score_rows_split<ARIDE_SCORE_UNROLL>), dim3((unsigned)R), dim3(256), 0, st,
-                                  sweep_start, sweep_stop, 0, logits, R, V, stride, tokens, tok_logp, tok_ent,
-                                  status);
-        else
-            hipLaunchKernelGGL((k_score_rows_split<ARIDE_SCORE_UNROLL>), dim3((unsigned)R), dim3(256), 0, st, logits,
-                               R, V, stride, tokens, tok_logp, tok_ent, status);
-    } else {
+    constexpr int U = ARIDE_SCORE_UNROLL;
+    const int nvec = V >> 3;                                  // 16-byte vectors per row
+    const bool fits_grid = R <= 0x7ffffff0ll;                 // one workgroup per row
+    const dim3 rows8(round_up_8((unsigned)(fits_grid ? R : 0)));
+    if (fits_grid && nvec >= kSplit16MinVec)
+        launch_sweep(k_score_rows_split<U, 16>, rows8, dim3(1024), st, sweep_start, sweep_stop, logits, R, V, stride,
+                     tokens, tok_logp, tok_ent, status);
+    else if (fits_grid && nvec >= kSplit8MinVec)
+        launch_sweep(k_score_rows_split<U, 8>, rows8, dim3(512), st, sweep_start, sweep_stop, logits, R, V, stride,
+                     tokens, tok_logp, tok_ent, status);
+    else if (fits_grid && nvec >= kSplit4MinVec)
+        launch_sweep(k_score_rows_split<U, 4>, rows8, dim3(256), st, sweep_start, sweep_stop, logits, R, V, stride,
+                     tokens, tok_logp, tok_ent, status);
+    else {
         long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
 #if ARIDE_SCORE_XCD_CHUNK == 0
         blocks = (blocks + 7) / 8 * 8;                       // the kernel's row mapping wants a multiple of 8
 #else
         blocks = (blocks + 8 * ARIDE_SCORE_XCD_CHUNK - 1) / (8 * ARIDE_SCORE_XCD_CHUNK) * (8 * ARIDE_SCORE_XCD_CHUNK);
 #endif
-        if (timed)
-            hipExtLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
-                                  dim3(64 * ARIDE_SCORE_WAVES), 0, st, sweep_start, sweep_stop, 0, logits, R, V,
-                                  stride, tokens, tok_logp, tok_ent, status);
-        else
-            hipLaunchKernelGGL((k_score_rows<ARIDE_SCORE_UNROLL>), dim3((unsigned)blocks),
-                               dim3(64 * ARIDE_SCORE_WAVES), 0, st, logits, R, V, stride, tokens, tok_logp, tok_ent,
-                               status);
+        launch_sweep(k_score_rows<U>, dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES), st, sweep_start,
+                     sweep_stop, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!step_logp && !step_ent)) return err;

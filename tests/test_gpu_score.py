@@ -241,9 +241,10 @@ def test_timed_entry_point_gives_the_same_results_and_a_kernel_time():
     assert err.value.rc == b.E_NULL
 
 
-@pytest.mark.parametrize("V,stride_pad", [(8192, 0), (8193, 3), (8199, 1), (12345, 5), (16384 + 511, 2), (65536, 0)])
-def test_four_waves_per_row_path(oracle, V, stride_pad):
-    # few rows of a long vocabulary: each row is split over the four waves of a workgroup
+@pytest.mark.parametrize("V,stride_pad", [(8192, 0), (8193, 3), (8199, 1), (12345, 5), (16384 + 511, 2), (65536, 0),
+                                          (151936, 0), (200001, 7)])
+def test_several_waves_per_row_path(oracle, V, stride_pad):
+    # long rows: each is shared by the 4, 8 or 16 waves of a workgroup
     print(f"case V={V} pad={stride_pad}", flush=True)
     N, A = 5, 3
     R = N * A
@@ -268,13 +269,16 @@ def test_four_waves_per_row_path(oracle, V, stride_pad):
     assert got["tok_logp"][8] == 0 and got["tok_ent"][8] == 0 and got["tok_logp"][9] == 0
 
 
-def test_both_sweeps_agree_at_the_row_count_where_they_switch(oracle):
-    V = 9000
-    logits = synth.logits_bf16(4097, V, seed=950, device=DEV)
-    tokens = synth.action_tokens(logits, seed=951)
-    a, _ = run_gpu(logits[:4096].contiguous(), tokens[:4096].contiguous(), 1)     # four waves per row
-    c, _ = run_gpu(logits, tokens, 1)                                             # one wave per row
-    want = oracle.score_logits(bits_of(logits), npf(tokens), 1, nthreads=8)
-    for k in ("tok_logp", "tok_ent"):
-        assert_close(c[k], want[k], 1.0 if k == "tok_logp" else ent_floor(V), f"one wave per row {k}")
-        assert_close(a[k], want[k][:4096], 1.0 if k == "tok_logp" else ent_floor(V), f"four waves per row {k}")
+@pytest.mark.parametrize("V", [8184, 8192, 24568, 24576, 98296, 98304, 98304 + 8 * 16 * 64 + 3])
+def test_row_lengths_where_the_number_of_waves_per_row_changes(oracle, V):
+    # rows below 16 KB take one wave each; from 1024, 3072 and 12288 16-byte vectors on a row is
+    # shared by 4, 8 and 16 waves
+    print(f"case V={V}", flush=True)
+    R, A = 10, 2
+    logits = synth.logits_bf16(R, V + 3, seed=950 + V, device=DEV, heavy_tail=True)
+    tokens = synth.action_tokens(logits[:, :V].contiguous(), seed=951 + V)
+    tokens[3] = -1
+    got, flags = run_gpu(logits, tokens, A, V=V)
+    want = oracle.score_logits(bits_of(logits), npf(tokens), A, V=V, nthreads=8)
+    compare(got, want, V, A, f"V={V}")
+    assert flags == 0
