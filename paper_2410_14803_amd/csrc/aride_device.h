@@ -109,14 +109,33 @@ __device__ __forceinline__ long long xcd_contiguous_block() {
 }
 inline unsigned round_up_8(unsigned blocks) { return (blocks + 7u) / 8u * 8u; }
 
+// Cross-lane moves inside a row of 16 lanes as DPP operands of ordinary vector instructions (no
+// trip through the LDS crossbar, which is what __shfl costs).  CTRL: 0x120 | n rotates the row
+// by n lanes, 0x110 | n shifts it right by n (lanes without a source read 0), 0x00..0xFF permute
+// each quad of lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// Wave-wide maximum / sum, left in every lane: rotations by 8, 4, 2, 1 inside each row of 16
+// lanes (both operands of every step are the same pair in all lanes that share them, so all
+// lanes end with the same bits), then the four rows are combined with two shuffles.
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, kWave));
+    v = fmaxf(v, dpp_f32<0x128>(v));
+    v = fmaxf(v, dpp_f32<0x124>(v));
+    v = fmaxf(v, dpp_f32<0x122>(v));
+    v = fmaxf(v, dpp_f32<0x121>(v));
+    v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    v = fmaxf(v, __shfl_xor(v, 32, kWave));
     return v;
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    v += dpp_f32<0x128>(v);
+    v += dpp_f32<0x124>(v);
+    v += dpp_f32<0x122>(v);
+    v += dpp_f32<0x121>(v);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
     return v;
 }
 __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
