@@ -129,6 +129,14 @@ __device__ __forceinline__ float wave_max(float v) {
     v = fmaxf(v, __shfl_xor(v, 32, kWave));
     return v;
 }
+// Sum over a row of 16 lanes, left in all of them.
+__device__ __forceinline__ float row_sum_f32(float v) {
+    v += dpp_f32<0x128>(v);
+    v += dpp_f32<0x124>(v);
+    v += dpp_f32<0x122>(v);
+    v += dpp_f32<0x121>(v);
+    return v;
+}
 __device__ __forceinline__ float wave_sum(float v) {
     v += dpp_f32<0x128>(v);
     v += dpp_f32<0x124>(v);

@@ -282,26 +282,26 @@ __global__ __launch_bounds__(64 * WPR) void k_score_rows_split(
     if (lane == 0) { part[wave][0] = Mw; part[wave][1] = s; part[wave][2] = t; }
     __syncthreads();             // every wave of the workgroup gets here: nothing above returns
 
-    if (threadIdx.x == 0) {
-        float lp = 0.f, en = 0.f;
-        if (live) {
-            float M = part[0][0];
+    // lane w of wave 0 brings wave w's state to the row's reference; the row of 16 lanes sums them
+    if (wave == 0) {
+        float M = part[0][0];
 #pragma unroll
-            for (int w = 1; w < WPR; ++w) M = fmaxf(M, part[w][0]);
-            const float kc = M * kLog2e;
-            float S = 0.f, T = 0.f;
-#pragma unroll
-            for (int w = 0; w < WPR; ++w) {
-                float sw, tw;
-                to_common(-(part[w][0] * kLog2e), part[w][1], part[w][2], kc, sw, tw);
-                S += sw; T += tw;
+        for (int w = 1; w < WPR; ++w) M = fmaxf(M, part[w][0]);
+        const float kc = M * kLog2e;
+        float S = 0.f, T = 0.f;
+        if (lane < WPR) to_common(-(part[lane][0] * kLog2e), part[lane][1], part[lane][2], kc, S, T);
+        S = row_sum_f32(S);
+        T = row_sum_f32(T);
+        if (lane == 0) {
+            float lp = 0.f, en = 0.f;
+            if (live) {
+                const float logS = logf(S);
+                lp = kLn2 * fmaf(xtok, kLog2e, -kc) - logS;
+                en = logS - kLn2 * T / S;
             }
-            const float logS = logf(S);
-            lp = kLn2 * fmaf(xtok, kLog2e, -kc) - logS;
-            en = logS - kLn2 * T / S;
+            if (tok_logp) tok_logp[row] = lp;
+            if (tok_ent) tok_ent[row] = en;
         }
-        if (tok_logp) tok_logp[row] = lp;
-        if (tok_ent) tok_ent[row] = en;
     }
 }
 
