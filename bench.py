@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
 # plain 1 GiB copy kernel.  Valid only for the kernel source it was measured on (first 16 hex
 # digits of its sha256) and for the learner-batch workload; reported as null otherwise.
-TRAFFIC = {"source_sha256": "742b3f85550ebb93", "config": 1, "logit_rows": 82144,
-           "bytes_per_launch": 5287430885}
+TRAFFIC = {"source_sha256": "bedbb44b7456ad9e", "config": 1, "logit_rows": 82144,
+           "bytes_per_launch": 5287516475}
 # The same for the gradient sweep (profiles/k_actor_grad_learner_batch.md), scaled by the factors the copy gave.
 TRAFFIC_ACTOR = {"source_sha256": "ae2247054849a908", "config": 1, "logit_rows": 82144,
                  "bytes_per_launch": 10564834816}
