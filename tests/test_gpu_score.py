@@ -212,10 +212,11 @@ def test_accuracy_does_not_depend_on_the_logits_magnitude(oracle, offset):
     compare(got, want, V, A, f"offset {offset}")
 
 
-def test_timed_entry_point_gives_the_same_results_and_a_kernel_time():
+@pytest.mark.parametrize("V", [500, 32128, 151936])      # one wave per row, 8 and 16 waves per row
+def test_timed_entry_point_gives_the_same_results_and_a_kernel_time(V):
     import time
     cfg = synth.CONFIGS[0]
-    R, V, A = 2560, cfg.V, cfg.A
+    R, A = 2560 if V < 100000 else 512, cfg.A
     logits = synth.logits_bf16(R, V, seed=77, device=DEV)
     tokens = synth.action_tokens(logits, seed=78)
     ws = b.Workspace(0)
@@ -233,7 +234,7 @@ def test_timed_entry_point_gives_the_same_results_and_a_kernel_time():
     for p, t in zip(plain, timed):
         assert torch.equal(p, t)
     ms = e0.elapsed_time(e1)
-    assert 0.005 < ms <= wall_ms, (ms, wall_ms)    # 164 MB cannot be read in under 5 us
+    assert R * V * 2 / 8e12 * 1e3 < ms <= wall_ms, (ms, wall_ms)    # no faster than the memory's peak rate
     # both events are required
     with pytest.raises(b.ArideError) as err:
         b._check("aride_score_logits_timed", b.lib().aride_score_logits_timed(
