@@ -234,7 +234,8 @@ def test_timed_entry_point_gives_the_same_results_and_a_kernel_time(V):
     for p, t in zip(plain, timed):
         assert torch.equal(p, t)
     ms = e0.elapsed_time(e1)
-    assert R * V * 2 / 8e12 * 1e3 < ms <= wall_ms, (ms, wall_ms)    # no faster than the memory's peak rate
+    # no faster than twice the HBM peak rate (a batch this small may sit in the last-level cache)
+    assert R * V * 2 / 16e12 * 1e3 < ms <= wall_ms, (ms, wall_ms)
     # both events are required
     with pytest.raises(b.ArideError) as err:
         b._check("aride_score_logits_timed", b.lib().aride_score_logits_timed(
