@@ -19,7 +19,7 @@ def test_score_and_actor_grad_random_shapes(oracle):
     for case in range(40):
         A = int(rng.integers(1, 9))
         N = int(rng.integers(1, 7))
-        V = int(rng.choice([1, 2, 3, 9, 17, 63, 64, 65, 127, 255, 257, 511, 1000, 1023, 1025, 4097, 9000]))
+        V = int(rng.choice([1, 2, 3, 9, 17, 63, 64, 65, 127, 255, 257, 511, 1000, 1023, 1025, 4097, 9000, 25001, 100003]))
         pad = int(rng.integers(0, 9))
         R = N * A
         print(f"case {case}: N={N} A={A} V={V} pad={pad}", flush=True)
