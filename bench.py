@@ -312,7 +312,9 @@ def main():
     from paper_2410_14803_amd import binding as b
     from paper_2410_14803_amd import synth
 
-    b.lib()   # fail loudly if the HIP library is missing
+    from paper_2410_14803_amd import build as hip_build
+    hip_build.ensure_built()   # compiles only a tree with nothing built
+    b.lib()   # fails loudly if the HIP library is still missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.path == "retrace":

@@ -44,6 +44,13 @@ def build(verbose: bool = False, extra=None, out: str = LIB) -> str:
     return out
 
 
+def ensure_built(verbose: bool = False) -> str:
+    """Builds only if nothing is built (tests, smoke and bench call this; the binding itself never builds)."""
+    if not (os.path.exists(LIB) and os.path.exists(PROBE_LIB)):
+        build(verbose=verbose)
+    return LIB
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     sys.exit(0)
