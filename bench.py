@@ -131,6 +131,13 @@ def bench_retrace(args, b, torch, synth, dev):
     def step():
         b.retrace_targets(lp, lm, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"], target=tg, td=td, rho=rho)
         b.compute_priorities(td, rho, ent, off, cfg.w, step_prio=sp, traj_prio=tp)
+    # the two sibling kernels of the same scan, a few untimed calls each so that a profile of this
+    # command shows them too: V-trace targets and Monte-Carlo returns
+    ret, lab = f(N), f(N)
+    for _ in range(10):
+        b.retrace_targets(lp, lm, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"], target=tg, td=td,
+                          rho=rho, vtrace=True, rho_bar=1.0, c_bar=1.0)
+        b.mc_returns(si["reward"], off, cfg.gamma, ret=ret, label=lab)
     elapsed, ms = _timed(torch, step, args.steps, args.warmup)
     alg_bytes = N * (20 + 12) + N * (12 + 4) + cfg.B * 12     # retrace: 5 in + 3 out; priorities: 3 in + 1 out
     cpu = None
