@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 TRAFFIC = {"source_sha256": "bedbb44b7456ad9e", "config": 1, "logit_rows": 82144,
            "bytes_per_launch": 5287516475}
 # The same for the gradient sweep (profiles/k_actor_grad_learner_batch.md), scaled by the factors the copy gave.
-TRAFFIC_ACTOR = {"source_sha256": "4245dd062d319089", "config": 1, "logit_rows": 82144,
-                 "bytes_per_launch": 10558627635}
+TRAFFIC_ACTOR = {"source_sha256": "968433073b711765", "config": 1, "logit_rows": 82144,
+                 "bytes_per_launch": 10559293543}
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 

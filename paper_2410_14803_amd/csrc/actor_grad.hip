@@ -8,7 +8,7 @@
 // log Z is carried as a two-float value, so p_v = exp(x_v - log Z) is accurate to a few fp32
 // ulps whatever the magnitude of the logits, and the chosen token's element, where 1 - p
 // cancels when the token dominates its row, is formed from expm1(tok_logp) instead.
-// One wave per row, 16-byte non-temporal loads and stores; HBM-bound, no MFMA.
+// Non-temporal loads and 16-byte non-temporal stores; HBM-bound, no MFMA.
 #include "aride_device.h"
 
 namespace aride {
@@ -17,11 +17,15 @@ namespace aride {
 #define ARIDE_ACTOR_NT_STORE 1  // non-temporal stores for the gradient
 #endif
 #ifndef ARIDE_ACTOR_UNROLL
-#define ARIDE_ACTOR_UNROLL 4   // 16-byte loads in flight per lane
+#define ARIDE_ACTOR_UNROLL 4   // 16-byte loads in flight per lane (bf16 output)
+#endif
+#ifndef ARIDE_ACTOR_UNROLL_F32
+#define ARIDE_ACTOR_UNROLL_F32 8   // 8-byte loads in flight per lane (fp32 output)
 #endif
 
 constexpr float kLog2eA = 1.4426950408889634f;
 constexpr float kLn2A = 0.6931471805599453f;
+constexpr int kSplit8MinV = 8192, kSplit16MinV = 12288;   // row lengths from which a row gets 8 and 16 waves
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -53,16 +57,24 @@ __device__ __forceinline__ uint16_t pack_bf16_one(float v) {
     return (uint16_t)(pack_bf16(v, 0.f) & 0xffffu);
 }
 
-// WPR = 1: one wave per row, four rows per workgroup.  WPR = 4: a workgroup of four waves per
-// row, each wave a contiguous quarter of the row's 16-byte vectors (wave 0 also the unaligned
-// head and tail), the rows dealt to the chip's 8 XCDs in contiguous eighths -- a bare copy of
-// this shape runs 9 % faster than one with a wave per row (see xcd_contiguous_block).
+// WPR = 1: one wave per row, four rows per workgroup.  WPR = 8, 16: a workgroup of that many
+// waves per row, the rows dealt to the chip's 8 XCDs in contiguous eighths (see
+// xcd_contiguous_block); the waves move along the row side by side, the workgroup covering
+// WPR KB of it per load instruction, so that a row is read and its gradient written as one
+// moving front.  Measured on 64 KB rows: 16 waves 1.71 ms per 5.3 GB batch, 8 waves 1.81, 4 waves
+// 1.93, one wave per row 2.02.
+// A lane's unit is 8 elements (16 bytes in, 16 out) for bf16 output and 4 elements (8 bytes in,
+// 16 out) for fp32 output, so that every store instruction of a wave writes 1 KB without gaps.
 template <bool OUT_F32, int WPR>
-__global__ __launch_bounds__(256) void k_actor_grad(
+__global__ __launch_bounds__(WPR == 1 ? 256 : 64 * WPR) void k_actor_grad(
     const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, int A, const float* __restrict__ tok_logp,
     const float* __restrict__ tok_ent, const float* __restrict__ rho, const float* __restrict__ target,
     const float* __restrict__ baseline, float beta, float scale, void* __restrict__ grad_out) {
+    constexpr int kVec = OUT_F32 ? 4 : 8;            // elements per lane and load
+    constexpr int kWords = kVec / 2;
+    constexpr uint32_t kVecBytes = 2 * kVec;
+    typedef uint32_t vec_t __attribute__((ext_vector_type(kWords)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long long row = WPR == 1 ? (((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6)
                                    : xcd_contiguous_block();   // the grid is R rounded up to a multiple of 8
@@ -73,10 +85,12 @@ __global__ __launch_bounds__(256) void k_actor_grad(
     uint16_t* gb = reinterpret_cast<uint16_t*>(grad_out) + row * row_stride;
     float* gf = reinterpret_cast<float*>(grad_out) + row * row_stride;
 
-    int head = (int)(((16u - (uint32_t)((uintptr_t)p & 15u)) & 15u) >> 1);
+    // elements before the first aligned load; both bases are 16-byte aligned, so the stores of
+    // the vectors that follow are 16-byte aligned as well
+    int head = (int)(((kVecBytes - (uint32_t)((uintptr_t)p & (kVecBytes - 1))) & (kVecBytes - 1)) >> 1);
     if (head > V) head = V;
-    const int nvec = (V - head) >> 3;
-    const int tail0 = head + (nvec << 3);
+    const int nvec = (V - head) / kVec;
+    const int tail0 = head + nvec * kVec;
 
     RowCoef c;
     c.negkz = 0.f; c.negkz_lo = 0.f; c.cbl = 0.f; c.k1 = 0.f; c.coef = 0.f;
@@ -97,30 +111,29 @@ __global__ __launch_bounds__(256) void k_actor_grad(
         const float pm1 = expm1f(lp);
         gtok = fmaf(c.coef, pm1, cb * (1.f + pm1) * (lp + h));
     }
-    const int tvec = (live && tok >= head && tok < tail0) ? ((tok - head) >> 3) : -1;
-    const int tsub = (tok - head) & 7;
+    const int tvec = (live && tok >= head && tok < tail0) ? ((tok - head) / kVec) : -1;
+    const int tsub = (tok - head) & (kVec - 1);
 
-    const u32x4* pv = reinterpret_cast<const u32x4*>(p + head);
-    auto emit = [&](int i, const u32x4& v) {
-        float g[8];
+    const vec_t* pv = reinterpret_cast<const vec_t*>(p + head);
+    auto emit = [&](int i, const vec_t& v) {
+        float g[kVec];
         if (live) {
-            g[0] = grad_of(bits_to_float(v.x << 16), c); g[1] = grad_of(bits_to_float(v.x & 0xffff0000u), c);
-            g[2] = grad_of(bits_to_float(v.y << 16), c); g[3] = grad_of(bits_to_float(v.y & 0xffff0000u), c);
-            g[4] = grad_of(bits_to_float(v.z << 16), c); g[5] = grad_of(bits_to_float(v.z & 0xffff0000u), c);
-            g[6] = grad_of(bits_to_float(v.w << 16), c); g[7] = grad_of(bits_to_float(v.w & 0xffff0000u), c);
+#pragma unroll
+            for (int w = 0; w < kWords; ++w) {
+                g[2 * w] = grad_of(bits_to_float(v[w] << 16), c);
+                g[2 * w + 1] = grad_of(bits_to_float(v[w] & 0xffff0000u), c);
+            }
             if (i == tvec) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) g[j] = (j == tsub) ? gtok : g[j];
+                for (int j = 0; j < kVec; ++j) g[j] = (j == tsub) ? gtok : g[j];
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) g[j] = 0.f;
+            for (int j = 0; j < kVec; ++j) g[j] = 0.f;
         }
         if constexpr (OUT_F32) {
-            f32x4* o = reinterpret_cast<f32x4*>(gf + head) + 2 * (long long)i;
-            f32x4 a = {g[0], g[1], g[2], g[3]}, b = {g[4], g[5], g[6], g[7]};
-            __builtin_nontemporal_store(a, o);
-            __builtin_nontemporal_store(b, o + 1);
+            f32x4 o = {g[0], g[1], g[2], g[3]};
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(gf + head) + i);
         } else {
             u32x4 o = {pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3]), pack_bf16(g[4], g[5]), pack_bf16(g[6], g[7])};
 #if ARIDE_ACTOR_NT_STORE
@@ -130,25 +143,25 @@ __global__ __launch_bounds__(256) void k_actor_grad(
 #endif
         }
     };
-    constexpr int kU = ARIDE_ACTOR_UNROLL;
-    // this wave's share of the row's vectors: whole 1 KB pieces
-    const int share = WPR == 1 ? nvec : ((((nvec + WPR - 1) / WPR) + kWave - 1) & ~(kWave - 1));
-    const int vend = WPR == 1 ? nvec : min(nvec, (wave + 1) * share);
-    int i = (WPR == 1 ? 0 : wave * share) + lane;
+    constexpr int kU = OUT_F32 ? ARIDE_ACTOR_UNROLL_F32 : ARIDE_ACTOR_UNROLL;
+    constexpr int kStep = WPR * kWave;               // vectors the row's waves cover per load
+    int i = (WPR == 1 ? 0 : wave * kWave) + lane;
     if (live) {
-        for (; i + (kU - 1) * kWave < vend; i += kU * kWave) {
-            u32x4 v[kU];
+        for (; i + (kU - 1) * kStep < nvec; i += kU * kStep) {
+            vec_t v[kU];
 #pragma unroll
-            for (int u = 0; u < kU; ++u) v[u] = __builtin_nontemporal_load(pv + i + u * kWave);
+            for (int u = 0; u < kU; ++u) v[u] = __builtin_nontemporal_load(pv + i + u * kStep);
 #pragma unroll
-            for (int u = 0; u < kU; ++u) emit(i + u * kWave, v[u]);
+            for (int u = 0; u < kU; ++u) emit(i + u * kStep, v[u]);
         }
-        for (; i < vend; i += kWave) emit(i, __builtin_nontemporal_load(pv + i));
+        for (; i < nvec; i += kStep) emit(i, __builtin_nontemporal_load(pv + i));
     } else {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        for (; i < vend; i += kWave) emit(i, zero);
+        vec_t zero;
+#pragma unroll
+        for (int w = 0; w < kWords; ++w) zero[w] = 0u;
+        for (; i < nvec; i += kStep) emit(i, zero);
     }
-    // elements before the first 16-byte boundary and after the last full vector
+    // elements before the first aligned vector and after the last full one
     if (WPR > 1 && wave != 0) return;
     for (int k = lane; k < head + (V - tail0); k += kWave) {
         const int v = k < head ? k : tail0 + (k - head);
@@ -191,15 +204,16 @@ hipError_t actor_launch(const uint16_t* logits, long long R, int V, long long st
                         const float* baseline, const float* penalty, float beta, float lambda_pen,
                         float scale, int grad_f32, void* grad, float* loss, hipStream_t st) {
     if (grad && R > 0) {
-        // rows of 16 KB and more: a workgroup per row (one workgroup per row must fit the grid)
-        const bool split = (V >> 3) >= 1024 && R <= 0x7ffffff0ll;
-        const dim3 grid(split ? round_up_8((unsigned)R) : (unsigned)((R + 3) / 4));
+        // rows of 16 KB and more: a workgroup of 8 waves per row, of 24 KB and more: of 16 waves
+        // (one workgroup per row must fit the grid)
+        const int wpr = (R > 0x7ffffff0ll || V < kSplit8MinV) ? 1 : V < kSplit16MinV ? 8 : 16;
+        const dim3 grid(wpr > 1 ? round_up_8((unsigned)R) : (unsigned)((R + 3) / 4));
         auto go = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, logits, R, V, stride, tokens, A, tok_logp, tok_ent,
-                               rho, target, baseline, beta, scale, grad);
+            hipLaunchKernelGGL(kernel, grid, dim3(wpr > 1 ? 64 * wpr : 256), 0, st, logits, R, V, stride, tokens, A,
+                               tok_logp, tok_ent, rho, target, baseline, beta, scale, grad);
         };
-        if (grad_f32) { if (split) go(k_actor_grad<true, 4>); else go(k_actor_grad<true, 1>); }
-        else          { if (split) go(k_actor_grad<false, 4>); else go(k_actor_grad<false, 1>); }
+        if (grad_f32) { if (wpr == 16) go(k_actor_grad<true, 16>); else if (wpr == 8) go(k_actor_grad<true, 8>); else go(k_actor_grad<true, 1>); }
+        else          { if (wpr == 16) go(k_actor_grad<false, 16>); else if (wpr == 8) go(k_actor_grad<false, 8>); else go(k_actor_grad<false, 1>); }
     }
     if (loss)
         hipLaunchKernelGGL(k_actor_loss, dim3(1), dim3(1024), 0, st, step_logp, step_ent, rho, target, baseline,

@@ -52,7 +52,8 @@ def check_grad(got32, got16, want, rho, target, base, ent_rows, A, beta, scale, 
 
 
 @pytest.mark.parametrize("V,pad,beta", [(1, 0, 0.1), (7, 1, 0.0), (64, 0, 0.01), (513, 3, 0.5), (2051, 5, 0.01),
-                                        (8200, 8, 0.02), (32128, 0, 0.01)])
+                                        (8190, 2, 0.02), (8200, 8, 0.02), (12287, 1, 0.01), (12288, 0, 0.01),
+                                        (32128, 0, 0.01), (33001, 3, 0.01)])
 def test_small_shapes(oracle, V, pad, beta):
     print(f"case V={V} pad={pad}", flush=True)
     N, A = 5, 4
