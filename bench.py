@@ -129,6 +129,10 @@ def bench_retrace(args, b, torch, synth, dev):
     tg, td, rho, sp, tp = f(N), f(N), f(N), f(N), f(cfg.B)
 
     def step():
+        if args.one_pass:
+            b.retrace_priorities(lp, lm, si["reward"], si["value"], ent, off, cfg.gamma, cfg.lam, cfg.w, q=si["q"],
+                                 target=tg, td=td, rho=rho, step_prio=sp, traj_prio=tp)
+            return
         b.retrace_targets(lp, lm, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"], target=tg, td=td, rho=rho)
         b.compute_priorities(td, rho, ent, off, cfg.w, step_prio=sp, traj_prio=tp)
     # the two sibling kernels of the same scan, a few untimed calls each so that a profile of this
@@ -140,6 +144,8 @@ def bench_retrace(args, b, torch, synth, dev):
         b.mc_returns(si["reward"], off, cfg.gamma, ret=ret, label=lab)
     elapsed, ms = _timed(torch, step, args.steps, args.warmup)
     alg_bytes = N * (20 + 12) + N * (12 + 4) + cfg.B * 12     # retrace: 5 in + 3 out; priorities: 3 in + 1 out
+    if args.one_pass:
+        alg_bytes = N * (24 + 16) + cfg.B * 12                # 6 in + 4 out: td and rho are not read back
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -161,8 +167,9 @@ def bench_retrace(args, b, torch, synth, dev):
         "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": cfg.B, "traj_steps": N,
-                   "gamma": cfg.gamma, "lambda": cfg.lam},
-        "roofline": {"bound": "hbm", "kernel": "k_retrace + k_priorities (two launches; launch-latency bound)",
+                   "gamma": cfg.gamma, "lambda": cfg.lam, "one_pass": bool(args.one_pass)},
+        "roofline": {"bound": "hbm", "kernel": "k_retrace with the priorities in the same pass (one launch; launch-latency bound)"
+                     if args.one_pass else "k_retrace + k_priorities (two launches; launch-latency bound)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
@@ -298,6 +305,9 @@ def main():
                          "retrace: retrace_targets + compute_priorities on the long-scan workload (config 3). "
                          "replay: sample + update + index rebuild on the 2^24-entry buffer (config 4). "
                          "insert: circular insert of 65 536 entries into that buffer, index patched")
+    ap.add_argument("--one-pass", action="store_true",
+                    help="with --path scoring or retrace: retrace_targets and compute_priorities as the one call "
+                         "aride_retrace_priorities (one launch, TD errors and ratios not read back)")
     ap.add_argument("--rebuild-every-insert", action="store_true",
                     help="with --path insert: follow every insert by a full index rebuild (the comparison)")
     ap.add_argument("--rotate", type=int, default=0,
@@ -369,10 +379,15 @@ def main():
     def one_step(i, ev=None):
         b.score_logits(logits_ring[i % copies], tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
                        step_logp=step_logp, step_ent=step_ent, sweep_events=ev)
-        b.retrace_targets(step_logp, logmu, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"],
-                          target=target, td=td, rho=rho)
-        b.compute_priorities(td, rho, step_ent, off, cfg.w, td_scale=2.0, ent_scale=ent_scale,
-                             step_prio=step_prio, traj_prio=traj_prio)
+        if args.one_pass:
+            b.retrace_priorities(step_logp, logmu, si["reward"], si["value"], step_ent, off, cfg.gamma, cfg.lam,
+                                 cfg.w, q=si["q"], td_scale=2.0, ent_scale=ent_scale, target=target, td=td, rho=rho,
+                                 step_prio=step_prio, traj_prio=traj_prio)
+        else:
+            b.retrace_targets(step_logp, logmu, si["reward"], si["value"], off, cfg.gamma, cfg.lam, q=si["q"],
+                              target=target, td=td, rho=rho)
+            b.compute_priorities(td, rho, step_ent, off, cfg.w, td_scale=2.0, ent_scale=ent_scale,
+                                 step_prio=step_prio, traj_prio=traj_prio)
         b.sample_prioritized(weights, uni[i], ws, idx, prob)
         b.update_priorities(weights, idx, step_prio[prio_src] if N < K else step_prio[:K], cfg.alpha, ws)
 
@@ -430,7 +445,7 @@ def main():
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": B, "traj_steps": N,
                    "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
                    "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha,
-                   "logit_copies_in_rotation": copies},
+                   "logit_copies_in_rotation": copies, "one_pass": bool(args.one_pass)},
         "roofline": {"bound": "hbm", "kernel": "k_score_rows_split (8 waves per row at this row length)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},

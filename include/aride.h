@@ -208,6 +208,24 @@ int aride_compute_priorities(const float* td, const float* rho, const float* ent
                              void* stream);
 
 /*
+ * retrace_priorities -- aride_retrace_targets and aride_compute_priorities (Sections 5.2 and
+ * 5.3) in one pass over the trajectories: the TD error and the ratio of a step go into its
+ * priority while the scan still holds them, so they are not read back (36 bytes of traffic per
+ * step instead of 48) and the two steps cost one launch.  target, td, rho and step_prio are
+ * exactly what the two calls give one after the other; traj_prio is the same mean summed in
+ * another order (fp32, fixed order, so repeated calls agree bit for bit).
+ *
+ *  Arguments as in the two calls; ent fp32 [N] is compute_priorities' entropy input.  All five
+ *  outputs are nullable.
+ * Errors: those of the two calls.  B == 0 is a no-op.
+ */
+int aride_retrace_priorities(const float* logp_pi, const float* logp_mu, const float* reward,
+                             const float* value, const float* q, const float* boot, const float* ent,
+                             const int32_t* traj_offsets, int64_t B, int64_t N,
+                             aride_retrace_cfg cfg, aride_prio_cfg pcfg, float* target, float* td,
+                             float* rho, float* step_prio, float* traj_prio, void* stream);
+
+/*
  * update_priorities -- Section 5.3, last sentence (priorities are recomputed under the
  * latest policy and overwritten) and Appendix A.4.2 (the buffer stores p^alpha):
  *     for k = 0..K-1 in order:  weights[idx[k]] = (float) pow(max(prio[k], 0), alpha)

@@ -21,6 +21,7 @@ MAX_REPLAY = 1 << 24
 
 EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
            "aride_score_logits", "aride_score_logits_timed", "aride_retrace_targets", "aride_compute_priorities",
+           "aride_retrace_priorities",
            "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns", "aride_replay_insert"]
 
 
@@ -75,6 +76,8 @@ def lib():
     L.aride_score_logits_timed.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     L.aride_retrace_targets.restype = ctypes.c_int
     L.aride_retrace_targets.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, RetraceCfg, vp, vp, vp, vp]
+    L.aride_retrace_priorities.restype = ctypes.c_int
+    L.aride_retrace_priorities.argtypes = [vp] * 8 + [i64, i64, RetraceCfg, PrioCfg] + [vp] * 6
     L.aride_compute_priorities.restype = ctypes.c_int
     L.aride_compute_priorities.argtypes = [vp, vp, vp, vp, i64, i64, PrioCfg, vp, vp, vp]
     L.aride_update_priorities.restype = ctypes.c_int
@@ -184,6 +187,24 @@ def compute_priorities(td, rho, ent, traj_offsets, w, td_scale=1.0, ent_scale=1.
     rc = lib().aride_compute_priorities(_p(td, f), _p(rho, f), _p(ent, f), _p(traj_offsets, torch.int32),
                                         B, N, cfg, _p(step_prio, f), _p(traj_prio, f), _stream())
     _check("aride_compute_priorities", rc)
+
+
+def retrace_priorities(logp_pi, logp_mu, reward, value, ent, traj_offsets, gamma, lam, w, q=None, boot=None,
+                       td_scale=1.0, ent_scale=1.0, eps=0.0, truncate_rho=True, target=None, td=None, rho=None,
+                       step_prio=None, traj_prio=None, vtrace=False, rho_bar=1.0, c_bar=1.0):
+    """retrace_targets and compute_priorities in one pass (one launch)."""
+    B = traj_offsets.numel() - 1
+    N = logp_pi.numel()
+    f = torch.float32
+    rcfg = RetraceCfg(float(gamma), float(lam), TRACE_VTRACE if vtrace else TRACE_RETRACE, float(rho_bar),
+                      float(c_bar))
+    pcfg = PrioCfg(float(w[0]), float(w[1]), float(w[2]), float(td_scale), float(ent_scale), float(eps),
+                   int(bool(truncate_rho)))
+    rc = lib().aride_retrace_priorities(_p(logp_pi, f), _p(logp_mu, f), _p(reward, f), _p(value, f), _p(q, f),
+                                        _p(boot, f), _p(ent, f), _p(traj_offsets, torch.int32), B, N, rcfg, pcfg,
+                                        _p(target, f), _p(td, f), _p(rho, f), _p(step_prio, f), _p(traj_prio, f),
+                                        _stream())
+    _check("aride_retrace_priorities", rc)
 
 
 def update_priorities(weights, idx, prio, alpha, ws):

@@ -8,7 +8,7 @@ hipError_t score_logits_launch(const uint16_t*, long long, int, long long, const
                                float*, float*, float*, uint32_t*, hipStream_t, hipEvent_t, hipEvent_t);
 hipError_t retrace_launch(const float*, const float*, const float*, const float*, const float*,
                           const float*, const int*, int, int, float, float, int, float, float, float*, float*,
-                          float*, hipStream_t);
+                          float*, const PrioArgs*, hipStream_t);
 hipError_t mc_returns_launch(const float*, const int*, int, int, float, float*, float*, hipStream_t);
 hipError_t priorities_launch(const float*, const float*, const float*, const int*, int, int, float,
                              float, float, float, float, float, int, float*, float*, hipStream_t);
@@ -101,20 +101,43 @@ int aride_score_logits_timed(const void* logits_bf16, int64_t R, int64_t V, int6
                                 ws, ws_bytes, stream, sweep_start, sweep_stop);
 }
 
+// Shared by aride_retrace_targets (pcfg == NULL) and aride_retrace_priorities.
+static int retrace_checked(const float* logp_pi, const float* logp_mu, const float* reward, const float* value,
+                           const float* q, const float* boot, const float* ent, const int32_t* traj_offsets,
+                           int64_t B, int64_t N, aride_retrace_cfg cfg, const aride_prio_cfg* pcfg, float* target,
+                           float* td, float* rho, float* step_prio, float* traj_prio, void* stream) {
+    if (B < 0 || N < 0) return ARIDE_E_SHAPE;
+    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (pcfg && (!(pcfg->td_scale != 0.f) || !(pcfg->ent_scale != 0.f))) return ARIDE_E_RANGE;
+    if (B == 0) return ARIDE_OK;
+    if (!traj_offsets) return ARIDE_E_NULL;
+    if (N > 0 && (!logp_pi || !logp_mu || !reward || !value || (pcfg && !ent))) return ARIDE_E_NULL;
+    if (cfg.mode != ARIDE_TRACE_RETRACE && cfg.mode != ARIDE_TRACE_VTRACE) return ARIDE_E_RANGE;
+    PrioArgs pa;
+    if (pcfg)
+        pa = PrioArgs{ent, pcfg->w_td, pcfg->w_rho, pcfg->w_ent, 1.f / pcfg->td_scale, 1.f / pcfg->ent_scale,
+                      pcfg->eps, pcfg->truncate_rho != 0, step_prio, traj_prio};
+    hipError_t err = retrace_launch(logp_pi, logp_mu, reward, value, q, boot, traj_offsets, (int)B,
+                                    (int)N, cfg.gamma, cfg.lambda, cfg.mode == ARIDE_TRACE_VTRACE, cfg.rho_bar,
+                                    cfg.c_bar, target, td, rho, pcfg ? &pa : nullptr, (hipStream_t)stream);
+    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
 int aride_retrace_targets(const float* logp_pi, const float* logp_mu, const float* reward,
                           const float* value, const float* q, const float* boot,
                           const int32_t* traj_offsets, int64_t B, int64_t N, aride_retrace_cfg cfg,
                           float* target, float* td, float* rho, void* stream) {
-    if (B < 0 || N < 0) return ARIDE_E_SHAPE;
-    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
-    if (B == 0) return ARIDE_OK;
-    if (!traj_offsets) return ARIDE_E_NULL;
-    if (N > 0 && (!logp_pi || !logp_mu || !reward || !value)) return ARIDE_E_NULL;
-    if (cfg.mode != ARIDE_TRACE_RETRACE && cfg.mode != ARIDE_TRACE_VTRACE) return ARIDE_E_RANGE;
-    hipError_t err = retrace_launch(logp_pi, logp_mu, reward, value, q, boot, traj_offsets, (int)B,
-                                    (int)N, cfg.gamma, cfg.lambda, cfg.mode == ARIDE_TRACE_VTRACE, cfg.rho_bar,
-                                    cfg.c_bar, target, td, rho, (hipStream_t)stream);
-    return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+    return retrace_checked(logp_pi, logp_mu, reward, value, q, boot, nullptr, traj_offsets, B, N, cfg, nullptr,
+                           target, td, rho, nullptr, nullptr, stream);
+}
+
+int aride_retrace_priorities(const float* logp_pi, const float* logp_mu, const float* reward,
+                             const float* value, const float* q, const float* boot, const float* ent,
+                             const int32_t* traj_offsets, int64_t B, int64_t N, aride_retrace_cfg cfg,
+                             aride_prio_cfg pcfg, float* target, float* td, float* rho, float* step_prio,
+                             float* traj_prio, void* stream) {
+    return retrace_checked(logp_pi, logp_mu, reward, value, q, boot, ent, traj_offsets, B, N, cfg, &pcfg, target,
+                           td, rho, step_prio, traj_prio, stream);
 }
 
 int aride_mc_returns(const float* reward, const int32_t* traj_offsets, int64_t B, int64_t N, float gamma,

@@ -152,4 +152,13 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
     return v;
 }
 
+// What compute_priorities needs when it rides along with the Retrace scan (k_retrace, PRIO).
+struct PrioArgs {
+    const float* ent;
+    float w_td, w_rho, w_ent, inv_td_scale, inv_ent_scale, eps;
+    int truncate;
+    float* step_prio;
+    float* traj_prio;
+};
+
 }  // namespace aride

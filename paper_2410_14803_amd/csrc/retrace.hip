@@ -57,18 +57,30 @@ __device__ __forceinline__ float tile_scan(float* sa, float* sb, int lane, float
     return __shfl(D.w, kWave - 1, kWave);
 }
 
+// Section 5.3 / Appendix A.4.3: p_t = w1*|delta_t|/s_delta + w2*rho~_t + w3*H_t/s_H + eps.
+__device__ __forceinline__ float step_priority(float td, float rho, float ent, float w_td, float w_rho,
+                                               float w_ent, float inv_td_scale, float inv_ent_scale,
+                                               float eps, int truncate) {
+    const float r = truncate ? fminf(1.f, rho) : rho;
+    return w_td * fabsf(td) * inv_td_scale + w_rho * r + w_ent * ent * inv_ent_scale + eps;
+}
+
 // VTRACE = false: Retrace(lambda) as in Section 5.2 -- the coefficient in front of Delta_{t+1}
 // is gamma*lambda*min(1, rho_{t+1}) and the additive term is delta_t.
 // VTRACE = true: the V-trace targets of IMPALA, which the paper contrasts Retrace with
 // (Section 2, Appendix A.4.1): additive term min(rho_bar, rho_t)*delta_t, coefficient
 // gamma*lambda*min(c_bar, rho_t) -- the step's OWN ratio, not its successor's.
-template <bool VTRACE>
+// PRIO = true: the priorities of Section 5.3 are formed in the same pass from the TD error and
+// the ratio the wave already holds (plus one more load per step, the entropy), and the
+// trajectory's mean priority from a wave sum: 36 bytes per step instead of the 48 the two
+// kernels move between them, and one launch instead of two.
+template <bool VTRACE, bool PRIO>
 __global__ __launch_bounds__(256) void k_retrace(
     const float* __restrict__ logp_pi, const float* __restrict__ logp_mu,
     const float* __restrict__ reward, const float* __restrict__ value,
     const float* __restrict__ q, const float* __restrict__ boot,
     const int* __restrict__ offsets, int B, int N, float gamma, float lambda, float rho_bar, float c_bar,
-    float* __restrict__ target, float* __restrict__ td, float* __restrict__ rho_out) {
+    float* __restrict__ target, float* __restrict__ td, float* __restrict__ rho_out, PrioArgs pa) {
     __shared__ __attribute__((aligned(16))) float lds_a[4][kTile];   // coefficient on Delta_{t+1}
     __shared__ __attribute__((aligned(16))) float lds_b[4][kTile];   // additive term, later Delta
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -82,21 +94,23 @@ __global__ __launch_bounds__(256) void k_retrace(
 
     float carry_delta = 0.f;  // Delta of the step just after this tile (0 past the end)
     float carry_c = 0.f;      // Retrace: c of that step (0 past the end: nothing follows the last step)
+    float prio_sum = 0.f;     // PRIO: this lane's share of the trajectory's priorities
     for (int end = hi; end > lo; end -= kTile) {
         // 1. coalesced loads; position p = 64*i + lane holds step t = end-1-p
-        float dlt[kPerLane], rho[kPerLane], qv[kPerLane];
+        float dlt[kPerLane], rho[kPerLane], qv[kPerLane], ev[kPerLane];
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) {
             const int t = end - 1 - (i * kWave + lane);
-            float d = 0.f, r = 0.f, qt = 0.f;
+            float d = 0.f, r = 0.f, qt = 0.f, e = 0.f;
             if (t >= lo) {
                 const float vt = value[t];
                 qt = q ? q[t] : vt;
                 const float vnext = (t == hi - 1) ? boot_b : value[t + 1];
                 d = reward[t] + gamma * vnext - qt;
                 r = expf(logp_pi[t] - logp_mu[t]);
+                if constexpr (PRIO) e = pa.ent[t];
             }
-            dlt[i] = d; rho[i] = r; qv[i] = qt;
+            dlt[i] = d; rho[i] = r; qv[i] = qt; ev[i] = e;
         }
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) {
@@ -128,9 +142,19 @@ __global__ __launch_bounds__(256) void k_retrace(
                 if (target) target[t] = qv[i] + sb[i * kWave + lane];
                 if (td) td[t] = dlt[i];
                 if (rho_out) rho_out[t] = rho[i];
+                if constexpr (PRIO) {
+                    const float p = step_priority(dlt[i], rho[i], ev[i], pa.w_td, pa.w_rho, pa.w_ent,
+                                                  pa.inv_td_scale, pa.inv_ent_scale, pa.eps, pa.truncate);
+                    if (pa.step_prio) pa.step_prio[t] = p;
+                    prio_sum += p;
+                }
             }
         }
         wave_lds_sync();   // the next tile overwrites the staging area
+    }
+    if constexpr (PRIO) {
+        prio_sum = wave_sum(prio_sum);   // fixed order: reproducible
+        if (pa.traj_prio && lane == 0) pa.traj_prio[b] = hi > lo ? prio_sum / (float)(hi - lo) : 0.f;
     }
 }
 
@@ -191,11 +215,9 @@ __global__ __launch_bounds__(256) void k_priorities(
         for (int i = 0; i < kPerLane; ++i) {
             const int t = t0 + i * kWave + lane;
             p[i] = 0.f;
-            if (t < hi) {
-                float r = rho[t];
-                if (truncate) r = fminf(1.f, r);
-                p[i] = w_td * fabsf(td[t]) * inv_td_scale + w_rho * r + w_ent * ent[t] * inv_ent_scale + eps;
-            }
+            if (t < hi)
+                p[i] = step_priority(td[t], rho[t], ent[t], w_td, w_rho, w_ent, inv_td_scale, inv_ent_scale, eps,
+                                     truncate);
         }
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) {
@@ -207,17 +229,19 @@ __global__ __launch_bounds__(256) void k_priorities(
     if (traj_prio && lane == 0) traj_prio[b] = hi > lo ? acc / (float)(hi - lo) : 0.f;
 }
 
+// pa == nullptr: targets only; otherwise the priorities are formed in the same pass.
 hipError_t retrace_launch(const float* lp, const float* lm, const float* r, const float* v,
                           const float* q, const float* boot, const int* off, int B, int N, float gamma,
                           float lambda, int vtrace, float rho_bar, float c_bar, float* target, float* td,
-                          float* rho, hipStream_t st) {
+                          float* rho, const PrioArgs* pa, hipStream_t st) {
     const unsigned blocks = (unsigned)(((long long)B * kWave + 255) / 256);
-    if (vtrace)
-        hipLaunchKernelGGL((k_retrace<true>), dim3(blocks), dim3(256), 0, st, lp, lm, r, v, q, boot, off, B, N,
-                           gamma, lambda, rho_bar, c_bar, target, td, rho);
-    else
-        hipLaunchKernelGGL((k_retrace<false>), dim3(blocks), dim3(256), 0, st, lp, lm, r, v, q, boot, off, B, N,
-                           gamma, lambda, rho_bar, c_bar, target, td, rho);
+    const PrioArgs none = {nullptr, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, nullptr, nullptr};
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, st, lp, lm, r, v, q, boot, off, B, N, gamma, lambda,
+                           rho_bar, c_bar, target, td, rho, pa ? *pa : none);
+    };
+    if (pa) { if (vtrace) go(k_retrace<true, true>); else go(k_retrace<false, true>); }
+    else    { if (vtrace) go(k_retrace<true, false>); else go(k_retrace<false, false>); }
     return hipGetLastError();
 }
 

@@ -104,6 +104,18 @@ def test_retrace_and_priorities_reject_bad_arguments(L):
     assert g(a, a, a, a, 2, 4, b.PrioCfg(1, 1, 1, 0, 1, 0, 1), a, a, None) == b.E_RANGE
     assert g(a, a, a, a, 2, 4, b.PrioCfg(1, 1, 1, 1, 0, 0, 1), a, a, None) == b.E_RANGE
     assert g(a, a, a, a, 0, 0, pc, a, a, None) == b.OK
+    # the two in one pass: the union of their checks
+    h = L.aride_retrace_priorities
+    assert h(a, a, a, a, None, None, a, a, -1, 4, cfg, pc, a, a, a, a, a, None) == b.E_SHAPE
+    assert h(a, a, a, a, None, None, a, a, 2, 1 << 31, cfg, pc, a, a, a, a, a, None) == b.E_RANGE
+    assert h(a, a, a, a, None, None, a, None, 2, 4, cfg, pc, a, a, a, a, a, None) == b.E_NULL     # offsets
+    assert h(a, a, a, a, None, None, None, a, 2, 4, cfg, pc, a, a, a, a, a, None) == b.E_NULL     # entropy
+    assert h(a, a, None, a, None, None, a, a, 2, 4, cfg, pc, a, a, a, a, a, None) == b.E_NULL     # reward
+    assert h(a, a, a, a, None, None, a, a, 2, 4, b.RetraceCfg(0.9, 0.95, 7, 1.0, 1.0), pc, a, a, a, a, a,
+             None) == b.E_RANGE
+    assert h(a, a, a, a, None, None, a, a, 2, 4, cfg, b.PrioCfg(1, 1, 1, 0, 1, 0, 1), a, a, a, a, a,
+             None) == b.E_RANGE
+    assert h(a, a, a, a, None, None, a, a, 0, 0, cfg, pc, a, a, a, a, a, None) == b.OK
 
 
 def test_replay_rejects_bad_arguments(L):

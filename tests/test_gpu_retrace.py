@@ -1,4 +1,5 @@
-"""GPU parity: aride_retrace_targets and aride_compute_priorities against the CPU oracle."""
+"""GPU parity: aride_retrace_targets, aride_compute_priorities and the two in one pass
+(aride_retrace_priorities) against the CPU oracle."""
 import numpy as np
 import pytest
 import torch
@@ -202,3 +203,80 @@ def test_mc_returns_ragged_and_signed(oracle):
     clear = np.abs(o_ret) > 1e-4
     np.testing.assert_array_equal(npf(label)[clear], o_label[clear])
     np.testing.assert_array_equal(npf(label), (npf(ret) > 0).astype(np.float32))
+
+
+def fused(lp, lm, si, ent, off, gamma, lam, w, q=None, boot=None, **kw):
+    N, B = lp.numel(), off.numel() - 1
+    out = {k: torch.full((N,), 7.0, device=DEV) for k in ("target", "td", "rho", "step_prio")}
+    out["traj_prio"] = torch.full((B,), 7.0, device=DEV)
+    b.retrace_priorities(lp, lm, si["reward"], si["value"], ent, off, gamma, lam, w, q=q, boot=boot, **out, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("lens", [[1], [0, 5, 0, 0, 7, 0], [63, 64, 65], [300, 1, 64, 1000, 2, 191, 192, 193, 256, 257, 512],
+                                  list(range(1, 80))])
+@pytest.mark.parametrize("vtrace", [False, True])
+def test_retrace_and_priorities_in_one_pass(oracle, lens, vtrace):
+    print(f"case lens={lens[:8]}... vtrace={vtrace}", flush=True)
+    cfg = synth.CONFIGS[3]
+    off_np, off, lp, lm, si, boot = make_case(lens, 900 + len(lens), cfg)
+    N = int(off_np[-1])
+    g = torch.Generator(device=DEV); g.manual_seed(17)
+    ent = torch.rand(N, generator=g, device=DEV) * 8
+    w = (1.0, 0.5, 0.1)
+    tr = dict(vtrace=True, rho_bar=1.3, c_bar=0.9) if vtrace else {}
+    for use_q, use_boot, trunc in ((False, False, True), (True, True, False)):
+        q = si["q"] if use_q else None
+        bt = boot if use_boot else None
+        kw = dict(td_scale=2.0, ent_scale=8.0, eps=1e-3, truncate_rho=trunc)
+        got = fused(lp, lm, si, ent, off, 0.99, 0.95, w, q=q, boot=bt, **kw, **tr)
+        okw = dict(q=None if q is None else npf(q), boot=None if bt is None else npf(bt))
+        if vtrace:
+            want = oracle.vtrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, 0.99, 0.95,
+                                         1.3, 0.9, **okw)
+        else:
+            want = oracle.retrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, 0.99, 0.95,
+                                          **okw)
+        for k in ("target", "td", "rho"):
+            assert_close(npf(got[k]), want[k], 1.0, f"one pass {k} q={use_q}")
+        # the priorities of the oracle, from the oracle's own TD errors and ratios
+        wp = oracle.compute_priorities(want["td"], want["rho"], npf(ent), off_np, *w, **kw)
+        assert_close(npf(got["step_prio"]), wp["step_prio"], 1.0, "one pass step_prio")
+        assert_close(npf(got["traj_prio"]), wp["traj_prio"], 1.0, "one pass traj_prio")
+        # and exactly what the two calls give one after the other
+        sep = {k: torch.full((N,), 7.0, device=DEV) for k in ("target", "td", "rho")}
+        b.retrace_targets(lp, lm, si["reward"], si["value"], off, 0.99, 0.95, q=q, boot=bt, **sep, **tr)
+        sp, tp = gpu_prio(sep["td"], sep["rho"], ent, off, w, **kw)
+        for k in ("target", "td", "rho"):
+            assert torch.equal(got[k], sep[k]), k
+        assert np.array_equal(npf(got["step_prio"]), sp)
+        assert_close(npf(got["traj_prio"]), tp, 1.0, "one pass traj_prio against two passes")
+
+
+def test_one_pass_on_config3_and_nullable_outputs(oracle):
+    cfg = synth.CONFIGS[3]
+    seed = synth.BASE_SEED + cfg.index
+    off_np = synth.trajectory_offsets(cfg, seed)
+    N = int(off_np[-1])
+    print(f"config3 one pass N={N}", flush=True)
+    off = torch.as_tensor(off_np, device=DEV)
+    lp = synth.policy_logprobs(N, seed + 3, DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 4, DEV)
+    lm = lp + si["mu_noise"]
+    ent = -lp                                        # the surprisal printed in Section 5.3
+    got = fused(lp, lm, si, ent, off, cfg.gamma, cfg.lam, cfg.w, boot=si["boot"])
+    want = oracle.retrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, cfg.gamma, cfg.lam,
+                                  boot=npf(si["boot"]))
+    wp = oracle.compute_priorities(want["td"], want["rho"], npf(ent), off_np, *cfg.w)
+    for k in ("target", "td", "rho"):
+        assert_close(npf(got[k]), want[k], 1.0, f"config3 one pass {k}")
+    assert_close(npf(got["step_prio"]), wp["step_prio"], 1.0, "config3 one pass step_prio")
+    assert_close(npf(got["traj_prio"]), wp["traj_prio"], 1.0, "config3 one pass traj_prio")
+    # every output may be left out; the others do not change
+    tp = torch.full((cfg.B,), 7.0, device=DEV)
+    b.retrace_priorities(lp, lm, si["reward"], si["value"], ent, off, cfg.gamma, cfg.lam, cfg.w, boot=si["boot"],
+                         traj_prio=tp)
+    b.retrace_priorities(lp, lm, si["reward"], si["value"], ent, off, cfg.gamma, cfg.lam, cfg.w)
+    torch.cuda.synchronize()
+    assert torch.equal(tp, got["traj_prio"])
