@@ -5,12 +5,14 @@
 // summation order gives the same answer:
 //     e = ilogb(max w) + 1,  q_i = floor(w_i * 2^(39-e)) < 2^39,  C_i = q_0 + ... + q_i (u64)
 //     t = min(floor(u * (double)Total), Total - 1),  idx = min{ i : C_i > t }
-// The index kept in the workspace has two levels: blocks of 256 weights (one wave x float4)
-// and super-blocks of 256 blocks.  block_cum holds, per super-block, the inclusive prefix of
-// its block sums; super_cum holds the inclusive prefix of the super-block totals (padded to
-// 256 entries with Total).  A draw is served by 16 lanes: the 256 super-block prefixes (staged
-// in LDS) and the 256 block prefixes of the chosen super-block are each searched 16-ary in two
-// probes, then the lanes quantise and scan the chosen block's 256 weights.
+// The index kept in the workspace has three levels of integer sums -- sub-blocks of 16 weights
+// (sub_sum), blocks of 256 weights (one wave x float4) and super-blocks of 256 blocks -- plus a
+// contiguous copy of every 16th block prefix (coarse_cum).  block_cum holds, per super-block, the
+// inclusive prefix of its block sums; super_cum the inclusive prefix of the super-block totals
+// (padded to 256 entries with Total).  A draw is served by 16 lanes: the 256 super-block prefixes
+// (staged in LDS) and the 256 block prefixes of the chosen super-block are each searched 16-ary in
+// two probes (the first probe of the latter reads coarse_cum, one line), then each lane reads one
+// of the block's 16 sub-block sums, and last the lanes quantise the chosen sub-block's 16 weights.
 //
 // Keeping the index current:
 //  * a rebuild of a large buffer is ONE sweep (k_super_sums<true>): it finds the maxima and
@@ -22,10 +24,13 @@
 //    whole buffer follows from the touched chunks alone and the index can be patched
 //    (k_insert_patch, k_patch_supers, k_patch_finish) instead of rebuilt.
 //
-// update_priorities resolves repeated indices without a serial loop: pass 1 writes the
-// tag (0xFF800000 | k) with an unsigned atomic max into the weight slot itself -- every
-// tag is larger than the bit pattern of any non-negative finite float, and the largest k
-// (the last occurrence) wins -- and pass 2 lets exactly the winning k store its weight.
+// update_priorities resolves repeated indices without a serial loop: pass 1 puts the tag
+// (0xFF800000 | k) into the weight slot itself with an unsigned atomic max -- every tag is larger
+// than the bit pattern of any float that is not -inf or a negative NaN, and the largest k (the
+// last occurrence) wins -- and pass 2 lets exactly the winning k store its weight.  A slot that
+// holds -inf or a negative NaN when the update starts (bits at or above the tag range) would beat
+// the tags; claim_slot recognises such a value by its not being a tag any occurrence of this batch
+// writes for this slot, and replaces it with a compare-and-swap.
 #include "aride_device.h"
 
 namespace aride {
@@ -53,13 +58,35 @@ __device__ __forceinline__ int exponent_of(uint32_t wmax_bits) {
     return (31 - __clz(mant)) - 149 + 1;
 }
 
+// Pass 1 for occurrence k of slot i (slot = the weight's word).  Afterwards the slot holds the
+// largest tag among the occurrences of i that have run so far, whatever bits it held before.
+//  * old value below the tag range: an ordinary weight, the atomic max has replaced it.
+//  * old value in the tag range whose low bits name an occurrence j < K with idx[j] == i: a tag of
+//    this batch for this slot (or a stored value with the very bits occurrence j writes, which
+//    changes nothing): the atomic max has merged mine with it.
+//  * otherwise a stored -inf or negative NaN.  If it is below my tag the atomic max has replaced
+//    it; if not, swap my tag in for exactly that value.  When the swap fails another occurrence
+//    has replaced it meanwhile and the next round finds that occurrence's tag.  The slot only ever
+//    moves from a stored value to a tag and from a tag to a larger tag, so at most one retry.
+__device__ __forceinline__ void claim_slot(uint32_t* slot, uint32_t k, const long long* __restrict__ idx, int K,
+                                           long long i) {
+    const uint32_t mine = kTagBase | k;
+    for (;;) {
+        const uint32_t old = atomicMax(slot, mine);
+        if (old < mine) return;
+        const uint32_t j = old & 0x7FFFFFu;
+        if (j < (uint32_t)K && idx[j] == i) return;
+        if (atomicCAS(slot, old, mine) == old) return;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_update_tag(
     float* __restrict__ weights, long long M, const long long* __restrict__ idx, int K, WsHeader* hdr) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= K) return;
     const long long i = idx[k];
     if (i < 0 || i >= M) { atomicOr(&hdr->flags, 0x8u); return; }
-    atomicMax(reinterpret_cast<uint32_t*>(weights) + i, kTagBase | (uint32_t)k);
+    claim_slot(reinterpret_cast<uint32_t*>(weights) + i, (uint32_t)k, idx, K, i);
 }
 
 __global__ __launch_bounds__(256) void k_update_commit(
@@ -86,7 +113,7 @@ __global__ __launch_bounds__(1024) void k_update_scatter_small(
     for (int k = threadIdx.x; k < K; k += 1024) {
         const long long i = idx[k];
         if (i < 0 || i >= M) { atomicOr(&hdr->flags, 0x8u); continue; }
-        atomicMax(wbits + i, kTagBase | (uint32_t)k);
+        claim_slot(wbits + i, (uint32_t)k, idx, K, i);
     }
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += 1024) {
@@ -758,7 +785,7 @@ __global__ __launch_bounds__(1024) void k_update_small(
     for (int k = tid; k < K; k += 1024) {
         const long long i = idx[k];
         if (i < 0 || i >= M) { atomicOr(&hdr->flags, 0x8u); continue; }
-        atomicMax(wbits + i, kTagBase | (uint32_t)k);
+        claim_slot(wbits + i, (uint32_t)k, idx, K, i);
     }
     __syncthreads();
     // 2. commit: exactly the winning k stores its weight

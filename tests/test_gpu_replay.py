@@ -165,9 +165,9 @@ def test_config_sample_then_update(oracle, ci):
 
 def test_config4_replay_at_scale_chain(oracle):
     # 100 iterations of sample -> recompute priorities from synthetic TD errors -> scatter -> rebuild.
-    # On the first five and every tenth iteration the oracle draws from the weight bits the device
-    # holds (bit-exact indices); a free-running oracle copy of the buffer, updated with the host's
-    # pow(), shows how far the last place of pow() lets the two drift.
+    # On EVERY iteration the oracle draws from the weight bits the device holds (bit-exact
+    # indices); on some, a free-running oracle copy of the buffer, updated with the host's pow(),
+    # shows how far the last place of pow() lets the two drift.
     cfg = synth.CONFIGS[4]
     seed = synth.BASE_SEED + cfg.index
     M, K = cfg.M, cfg.K
@@ -189,16 +189,14 @@ def test_config4_replay_at_scale_chain(oracle):
         idx, _ = gpu_sample(w, u, ws, want_prob=False)
         td = synth.td_errors(K, seed + 200 + it, DEV)
         prio = td.abs()                                   # w = (1, 0, 0): priority = |delta|
+        # the oracle draws from the weight bits the device holds ...
+        oi, _, rc = oracle.sample_prioritized(npf(w), npf(u))
+        np.testing.assert_array_equal(idx, oi, err_msg=f"iteration {it}")
         if it < 5 or it % 10 == 9:
-            # the oracle draws from the weight bits the device holds ...
-            oi, _, rc = oracle.sample_prioritized(npf(w), npf(u))
-            np.testing.assert_array_equal(idx, oi, err_msg=f"iteration {it}")
             # ... and, free-running from its own copy of the buffer, shows how far pow() lets the two drift
             fi, _, _ = oracle.sample_prioritized(free, npf(u))
             drift += int((fi != idx).sum())
             print(f"iter {it} ok, free-running index mismatches so far {drift}", flush=True)
-        else:
-            assert idx.min() >= 0 and idx.max() < M
         b.update_priorities(w, torch.as_tensor(idx, device=DEV), prio, cfg.alpha, ws)
         oracle.update_priorities(free, idx, npf(prio), cfg.alpha)    # same indices, host pow
     torch.cuda.synchronize()
@@ -277,3 +275,41 @@ def test_heavy_duplicates_in_a_large_batch(oracle):
     oracle.update_priorities(wo, npf(idx), npf(prio), 0.6)
     np.testing.assert_allclose(npf(w), wo, rtol=1e-6, atol=0)
     check_sample(oracle, w, synth.uniforms(2000, 45, DEV), ws, "heavy duplicates, large batch")
+
+
+@pytest.mark.parametrize("M,K", [(5000, 600), (20000, 600), (100000, 20000)])   # the three update routes
+@pytest.mark.parametrize("duplicates", [False, True])
+def test_update_overwrites_slots_that_hold_bad_bits(oracle, M, K, duplicates):
+    # Section 5.3, last sentence: the stored priority is overwritten, whatever it was.  Slots that hold
+    # -inf, negative NaNs (bit patterns at or above the tags the update passes through the slot), -1,
+    # -0 and a positive NaN are updated, once and several times per batch.
+    print(f"case M={M} K={K} duplicates={duplicates}", flush=True)
+    w = fresh(M, "exp", 50 + M, 0.6, oracle)
+    stale = [0xFFC00000, 0xFFFFFFFF, 0xFF800000, 0xBF800000, 0x80000000, 0x7FC00000,
+             0xFF800003, 0xFF800000 | (K - 1), 0xFF800000 | K, 0xFFBFFFFF]
+    slots = [3, 17, 255, 256, 1000, 2049, 4097, 4500, 4800, 4999]
+    wi = w.view(torch.int32)
+    for s, bits in zip(slots, stale):
+        wi[s] = int(np.array(bits, np.uint32).view(np.int32))
+    g = torch.Generator(device=DEV); g.manual_seed(60 + K)
+    idx = torch.randint(0, M, (K,), generator=g, device=DEV)
+    prio = torch.rand(K, generator=g, device=DEV) * 4 + 0.1
+    # every bad slot is updated: early and late in the batch, so that tags below and above the
+    # stored pattern's low bits occur
+    pos = torch.arange(len(slots), device=DEV)
+    idx[pos * 2 + 1] = torch.tensor(slots, device=DEV)
+    if duplicates:
+        idx[K - 1 - pos * 3] = torch.tensor(slots, device=DEV)
+        idx[K // 2 + pos] = torch.tensor(slots, device=DEV)
+        idx[3] = slots[6]                    # slot 4097 holds 0xFF800003: occurrence 3 updates that very slot
+    ws = b.Workspace(M)
+    wo = npf(w).copy()
+    b.update_priorities(w, idx, prio, 0.6, ws)
+    torch.cuda.synchronize()
+    oracle.update_priorities(wo, npf(idx), npf(prio), 0.6)
+    got = npf(w)
+    assert np.all(np.isfinite(got[slots])) and np.all(got[slots] > 0)
+    np.testing.assert_allclose(got, wo, rtol=1e-6, atol=0)
+    st, rc = ws.status()
+    assert rc == b.OK and not st.flags & b.ST_BAD_WEIGHT     # nothing bad is left in the buffer
+    check_sample(oracle, w, synth.uniforms(1000, 61, DEV), ws, "after overwriting bad slots")
