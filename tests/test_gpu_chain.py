@@ -7,26 +7,32 @@ import torch
 
 from paper_2410_14803_amd import binding as b
 from paper_2410_14803_amd import synth
-from _util import assert_close, bits_of, ent_floor, npf
+from _util import assert_close, bits_of, ent_floor, host_threads, npf, scored_config
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def run_chain(oracle, cfg, B=None):
-    if B is not None:
-        cfg = synth.scaled(cfg, B=B)
-    seed = synth.BASE_SEED + cfg.index
-    off_np = synth.trajectory_offsets(cfg, seed)
-    N = int(off_np[-1])
-    R = N * cfg.A
+def run_chain(oracle, cfg, full=False):
+    """full: the workload at its own size, logits and the oracle's reduction of every row taken from
+    the session's shared copy; otherwise the (small) workload is made and reduced here."""
+    if full:
+        case = scored_config(cfg.index)
+        seed, off_np, N, R, logits, tokens = (case[k] for k in ("seed", "off_np", "N", "R", "logits", "tokens"))
+        o_score = case["want"]
+    else:
+        seed = synth.BASE_SEED + cfg.index
+        off_np = synth.trajectory_offsets(cfg, seed)
+        N = int(off_np[-1])
+        R = N * cfg.A
+        logits = synth.logits_bf16(R, cfg.V, seed + 1, DEV, heavy_tail=cfg.heavy_tail)
+        tokens = synth.action_tokens(logits, seed + 2)
+        o_score = oracle.score_logits(bits_of(logits), npf(tokens), cfg.A, nthreads=host_threads())
+    print(f"chain {cfg.name}: B={cfg.B} N={N} R={R}", flush=True)
     off = torch.as_tensor(off_np, device=DEV)
-    logits = synth.logits_bf16(R, cfg.V, seed + 1, DEV, heavy_tail=cfg.heavy_tail)
-    tokens = synth.action_tokens(logits, seed + 2)
     si = synth.step_inputs(cfg, off_np, seed + 4, DEV)
 
     # ---- oracle chain (fp64 throughout)
-    o_score = oracle.score_logits(bits_of(logits), npf(tokens), cfg.A, nthreads=8)
     logmu = torch.as_tensor(o_score["step_logp"].astype(np.float32), device=DEV) + si["mu_noise"]
     o_rt = oracle.retrace_targets(o_score["step_logp"], npf(logmu), npf(si["reward"]), npf(si["value"]),
                                   off_np, cfg.gamma, cfg.lam, q=npf(si["q"]))
@@ -79,13 +85,72 @@ def test_chain_config0(oracle):
     run_chain(oracle, synth.CONFIGS[0])
 
 
-def test_chain_config1_reduced_batch(oracle):
-    # same per-step shapes as the learner batch, fewer trajectories so the oracle stays in seconds
-    run_chain(oracle, synth.CONFIGS[1], B=24)
+def test_chain_config1_full_batch(oracle):
+    # the learner batch at its own size: 256 trajectories, 82 144 logit rows
+    run_chain(oracle, synth.CONFIGS[1], full=True)
 
 
-def test_chain_config2_reduced_batch(oracle):
-    run_chain(oracle, synth.CONFIGS[2], B=2)
+def test_chain_config2_full_batch(oracle):
+    # the large-vocabulary batch at its own size: 128 trajectories of 16 steps, 131 072 rows of 151 936 logits
+    run_chain(oracle, synth.CONFIGS[2], full=True)
+
+
+@pytest.mark.parametrize("ci", [0, 1])
+def test_chain_trajectory_priorities_as_the_stored_key(oracle, ci):
+    # Section 5.3 gives a priority per trajectory, Appendix A.4.2 a circular buffer: score -> Retrace ->
+    # p(tau) -> circular insert with p(tau) as the stored key -> prioritized draw, device against oracle
+    cfg = synth.CONFIGS[ci]
+    case = scored_config(ci) if ci == 1 else None
+    if case is None:
+        seed = synth.BASE_SEED + cfg.index
+        off_np = synth.trajectory_offsets(cfg, seed)
+        N = int(off_np[-1]); R = N * cfg.A
+        logits = synth.logits_bf16(R, cfg.V, seed + 1, DEV, heavy_tail=cfg.heavy_tail)
+        tokens = synth.action_tokens(logits, seed + 2)
+        o_score = oracle.score_logits(bits_of(logits), npf(tokens), cfg.A, nthreads=host_threads())
+    else:
+        seed, off_np, N, R, logits, tokens = (case[k] for k in ("seed", "off_np", "N", "R", "logits", "tokens"))
+        o_score = case["want"]
+    off = torch.as_tensor(off_np, device=DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 4, DEV)
+    logmu = torch.as_tensor(o_score["step_logp"].astype(np.float32), device=DEV) + si["mu_noise"]
+    ent_scale = float(cfg.A * np.log(cfg.V))
+    o_rt = oracle.retrace_targets(o_score["step_logp"], npf(logmu), npf(si["reward"]), npf(si["value"]),
+                                  off_np, cfg.gamma, cfg.lam, q=npf(si["q"]))
+    o_pr = oracle.compute_priorities(o_rt["td"], o_rt["rho"], o_score["step_ent"], off_np, *cfg.w,
+                                     td_scale=2.0, ent_scale=ent_scale)
+    ws = b.Workspace(cfg.M)
+    f = lambda n: torch.empty(n, device=DEV)
+    tok_logp, tok_ent, step_logp, step_ent, traj_prio = f(R), f(R), f(N), f(N), f(cfg.B)
+    b.score_logits(logits, tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent, step_logp=step_logp, step_ent=step_ent)
+    b.retrace_priorities(step_logp, logmu, si["reward"], si["value"], step_ent, off, cfg.gamma, cfg.lam, cfg.w,
+                         q=si["q"], td_scale=2.0, ent_scale=ent_scale, traj_prio=traj_prio)
+    # the buffer holds earlier trajectories; the batch's B trajectories go in at a cursor near the
+    # end, so that the run wraps around
+    p0 = npf(synth.replay_priorities(cfg.M, cfg.replay, seed + 5, "cpu"))
+    w_host = np.zeros(cfg.M, np.float32)
+    oracle.update_priorities(w_host, np.arange(cfg.M), p0, cfg.alpha)
+    w = torch.as_tensor(w_host, device=DEV)
+    cursor = cfg.M - cfg.B // 3
+    slots = torch.full((cfg.B,), -7, dtype=torch.int64, device=DEV)
+    new_cursor = b.replay_insert(w, cursor, traj_prio, cfg.alpha, ws, slots_out=slots)
+    u = synth.uniforms(cfg.K, seed + 6, DEV)
+    idx = torch.empty(cfg.K, dtype=torch.int64, device=DEV)
+    prob = torch.empty(cfg.K, device=DEV)
+    b.sample_prioritized(w, u, ws, idx, prob)
+    torch.cuda.synchronize()
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0
+    assert_close(npf(traj_prio), o_pr["traj_prio"], 1.0, "p(tau)")
+    o_cursor, o_slots = oracle.replay_insert(w_host, cursor, o_pr["traj_prio"].astype(np.float32), cfg.alpha)
+    assert new_cursor == o_cursor == (cursor + cfg.B) % cfg.M
+    np.testing.assert_array_equal(npf(slots), o_slots)
+    assert_close(npf(w), w_host, 1.0, "stored weights")
+    oi, op, _ = oracle.sample_prioritized(npf(w), npf(u))       # from the device's weight bits
+    np.testing.assert_array_equal(npf(idx), oi)
+    np.testing.assert_allclose(npf(prob), op.astype(np.float32), rtol=1e-6)
+    # the newly stored trajectories can be drawn
+    assert np.isin(npf(idx), o_slots).any()
 
 
 def test_same_inputs_same_bits():

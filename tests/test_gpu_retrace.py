@@ -87,7 +87,7 @@ def test_special_cases_on_gpu():
     assert_close(out["target"], G, 1.0, "monte-carlo")
 
 
-@pytest.mark.parametrize("ci", [0, 1, 3])
+@pytest.mark.parametrize("ci", [0, 1, 2, 3])
 def test_config_shapes(oracle, ci):
     cfg = synth.CONFIGS[ci]
     seed = synth.BASE_SEED + cfg.index
@@ -169,7 +169,7 @@ def test_vtrace_config3_full(oracle):
     assert_close(npf(tgt), want["target"], 1.0, "vtrace config3")
 
 
-@pytest.mark.parametrize("ci", [0, 1, 3])
+@pytest.mark.parametrize("ci", [0, 1, 2, 3])
 def test_mc_returns(oracle, ci):
     cfg = synth.CONFIGS[ci]
     seed = synth.BASE_SEED + cfg.index

@@ -7,7 +7,7 @@ import torch
 
 from paper_2410_14803_amd import binding as b
 from paper_2410_14803_amd import synth
-from _util import assert_close, bits_of, ent_floor, npf
+from _util import assert_close, bits_of, ent_floor, npf, scored_config
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -112,52 +112,14 @@ def test_config0_full(oracle):
     assert flags == 0
 
 
-def _sampled_rows_check(oracle, cfg, logits, tokens, got, n_rows, n_steps, seed):
-    R = logits.shape[0]
-    g = np.random.default_rng(seed)
-    rows = np.unique(np.concatenate([[0, R - 1], g.integers(0, R, n_rows)]))
-    sub = bits_of(logits[torch.as_tensor(rows, device=DEV)])
-    want = oracle.score_logits(sub, npf(tokens)[rows], 1, nthreads=8)
-    assert_close(got["tok_logp"][rows], want["tok_logp"], 1.0, f"{cfg.name} sampled tok_logp")
-    assert_close(got["tok_ent"][rows], want["tok_ent"], ent_floor(cfg.V), f"{cfg.name} sampled tok_ent")
-    # whole steps: all A rows of a few steps
-    N = R // cfg.A
-    steps = np.unique(np.concatenate([[0, N - 1], g.integers(0, N, n_steps)]))
-    for n in steps:
-        sl = slice(n * cfg.A, (n + 1) * cfg.A)
-        w = oracle.score_logits(bits_of(logits[sl]), npf(tokens)[sl], cfg.A, nthreads=8)
-        assert_close(got["step_logp"][n:n + 1], w["step_logp"], 1.0, f"{cfg.name} step_logp[{n}]")
-        assert_close(got["step_ent"][n:n + 1], w["step_ent"], ent_floor(cfg.V), f"{cfg.name} step_ent[{n}]")
-    # properties that hold at any size
-    assert np.all(got["tok_logp"] <= 1e-5) and np.all(np.isfinite(got["tok_logp"]))
-    assert np.all(got["tok_ent"] >= -1e-5) and np.all(got["tok_ent"] <= math.log(cfg.V) + 1e-3)
-    np.testing.assert_allclose(got["step_logp"], got["tok_logp"].reshape(N, cfg.A).sum(1), rtol=1e-5, atol=1e-4)
-
-
-def test_config1_full_size_sampled(oracle):
-    cfg = synth.CONFIGS[1]
-    seed = synth.BASE_SEED + cfg.index
-    off = synth.trajectory_offsets(cfg, seed)
-    R = int(off[-1]) * cfg.A
-    print(f"config1 R={R}", flush=True)
-    logits = synth.logits_bf16(R, cfg.V, seed + 1, DEV)
-    tokens = synth.action_tokens(logits, seed + 2)
-    got, flags = run_gpu(logits, tokens, cfg.A)
-    assert flags == 0
-    _sampled_rows_check(oracle, cfg, logits, tokens, got, n_rows=600, n_steps=6, seed=11)
-
-
-def test_config2_full_size_sampled(oracle):
-    cfg = synth.CONFIGS[2]
-    seed = synth.BASE_SEED + cfg.index
-    off = synth.trajectory_offsets(cfg, seed)
-    R = int(off[-1]) * cfg.A
-    print(f"config2 R={R} bytes={R * cfg.V * 2 / 1e9:.1f} GB", flush=True)
-    logits = synth.logits_bf16(R, cfg.V, seed + 1, DEV, heavy_tail=True)
-    tokens = synth.action_tokens(logits, seed + 2)
-    got, flags = run_gpu(logits, tokens, cfg.A)
-    assert flags == 0
-    _sampled_rows_check(oracle, cfg, logits, tokens, got, n_rows=200, n_steps=2, seed=12)
+@pytest.mark.parametrize("ci", [1, 2])
+def test_config_full_size_every_row(ci):
+    # the learner batch (82 144 rows, 5.3 GB) and the large-vocabulary batch (131 072 rows of 304 KB,
+    # 39.8 GB): every row and every step against the oracle, which reads the logits in 1 GB chunks
+    case = scored_config(ci)
+    cfg, got = case["cfg"], {k: npf(v) for k, v in case["got"].items()}
+    assert case["flags"] == 0
+    compare(got, case["want"], cfg.V, cfg.A, f"config{ci}")
 
 
 def test_long_actions(oracle):
