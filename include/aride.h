@@ -284,6 +284,35 @@ int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t w
                              float* prob_out, void* stream);
 
 /*
+ * sample_prioritized_static -- aride_sample_prioritized for callers that cannot allocate device
+ * memory and so have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The sampling index is built and read in a fixed array that is
+ * part of the library's device code (ARIDE_STATIC_MAX_REPLAY sizes it: about 0.75 MB, held on
+ * every GPU the library runs on until the process ends), so the call needs only the inputs and
+ * outputs.  It allocates and frees nothing, and it does not synchronise.
+ *
+ * One call = the index of `weights` built as aride_update_priorities with K = 0 builds it (no
+ * weight is written), then the draws of aride_sample_prioritized: idx_out and prob_out are
+ * exactly what those two calls give with a workspace of the caller's.  The status block starts
+ * from zero on every call; status_out, when given, receives it (flags, total, wmax, exponent of
+ * this call alone).  A buffer with no mass gives idx_out[k] = -1 and ARIDE_ST_ZERO_MASS.
+ *
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two
+ * threads) race and must be serialised by the caller.  The array's address is looked up on the
+ * first call on each device (hipGetSymbolAddress, under a lock).
+ *
+ *  weights fp32 [M], 16-byte aligned, 1 <= M <= ARIDE_STATIC_MAX_REPLAY; uniforms fp64 [K];
+ *  idx_out int64 [K]; prob_out fp32 [K] nullable; status_out device aride_status [1], 8-byte
+ *  aligned, nullable.
+ * Errors: E_SHAPE (M <= 0, K < 0), E_RANGE (M > ARIDE_STATIC_MAX_REPLAY, K >= 2^25), E_NULL, E_ALIGN,
+ *         E_HIP (the array's address could not be obtained, or a launch failed).  K == 0 is a no-op.
+ */
+#define ARIDE_STATIC_MAX_REPLAY (1 << 20)
+int aride_sample_prioritized_static(const float* weights, int64_t M, const double* uniforms, int64_t K,
+                                    int64_t* idx_out, float* prob_out, aride_status* status_out /* device */,
+                                    void* stream);
+
+/*
  * actor_loss_grad -- Section 5.1, eq. (1) and the policy update of Appendix A.4.2: the actor
  * loss of a batch and its gradient with respect to the logits, as a second sweep over the
  * logits that aride_score_logits reduced.  With A_t = target[t] - baseline[t] (the

@@ -18,11 +18,13 @@ OK = 0
 E_NULL, E_SHAPE, E_ALIGN, E_RANGE, E_ZERO_MASS, E_WORKSPACE, E_HIP = -1, -2, -3, -4, -5, -6, -7
 ST_BAD_TOKEN, ST_BAD_WEIGHT, ST_ZERO_MASS, ST_BAD_INDEX, ST_BAD_UNIFORM = 1, 2, 4, 8, 16
 MAX_REPLAY = 1 << 24
+STATIC_MAX_REPLAY = 1 << 20
 
 EXPORTS = ["aride_workspace_bytes", "aride_workspace_init", "aride_status_read",
            "aride_score_logits", "aride_score_logits_timed", "aride_retrace_targets", "aride_compute_priorities",
            "aride_retrace_priorities",
-           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns", "aride_replay_insert"]
+           "aride_update_priorities", "aride_sample_prioritized", "aride_actor_loss_grad", "aride_mc_returns", "aride_replay_insert",
+           "aride_sample_prioritized_static"]
 
 
 class RetraceCfg(ctypes.Structure):
@@ -84,6 +86,8 @@ def lib():
     L.aride_update_priorities.argtypes = [vp, i64, vp, vp, i64, f32, vp, sz, vp]
     L.aride_sample_prioritized.restype = ctypes.c_int
     L.aride_sample_prioritized.argtypes = [vp, i64, vp, sz, vp, i64, vp, vp, vp]
+    L.aride_sample_prioritized_static.restype = ctypes.c_int
+    L.aride_sample_prioritized_static.argtypes = [vp, i64, vp, i64, vp, vp, vp, vp]
     L.aride_replay_insert.restype = ctypes.c_int
     L.aride_replay_insert.argtypes = [vp, i64, i64, vp, i64, f32, vp, vp, sz, ctypes.POINTER(ctypes.c_int64), vp]
     L.aride_mc_returns.restype = ctypes.c_int
@@ -220,6 +224,18 @@ def sample_prioritized(weights, uniforms, ws, idx_out, prob_out=None):
                                         _p(uniforms, torch.float64), uniforms.numel(),
                                         _p(idx_out, torch.int64), _p(prob_out, torch.float32), _stream())
     _check("aride_sample_prioritized", rc)
+
+
+def sample_prioritized_static(weights, uniforms, idx_out, prob_out=None, status_out=None):
+    """The draw without a workspace: the index lives in the library's own static device array.
+    status_out: uint8 [24] device tensor (or None) that receives this call's status block."""
+    if status_out is not None:
+        assert status_out.dtype == torch.uint8 and status_out.numel() >= ctypes.sizeof(Status)
+    rc = lib().aride_sample_prioritized_static(_p(weights, torch.float32), weights.numel(),
+                                               _p(uniforms, torch.float64), uniforms.numel(),
+                                               _p(idx_out, torch.int64), _p(prob_out, torch.float32),
+                                               _p(status_out), _stream())
+    _check("aride_sample_prioritized_static", rc)
 
 
 def actor_loss_grad(logits, tokens, A, tok_logp, tok_ent, step_logp, step_ent, rho, target, baseline,

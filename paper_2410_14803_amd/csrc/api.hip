@@ -2,6 +2,7 @@
 // Nothing here allocates, frees or waits (aride_status_read excepted, as documented).
 #include "aride.h"
 #include "aride_device.h"
+#include <mutex>
 
 namespace aride {
 hipError_t score_logits_launch(const uint16_t*, long long, int, long long, const int*, int, float*,
@@ -33,6 +34,37 @@ __global__ void k_fill_u64(unsigned long long* p, size_t n) {
 
 static inline size_t index_bytes(int64_t M) { return replay_index_bytes(M); }
 static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+// The first 24 bytes of a workspace header, copied to a caller's device buffer.
+__global__ void k_copy_status(const WsHeader* __restrict__ hdr, WsHeader* __restrict__ out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *out = *hdr;
+}
+
+// ---- The workspace of aride_sample_prioritized_static -----------------------------------------
+// Device memory that belongs to the library's code object, one copy per GPU, there from the moment
+// the code object is loaded until the process ends: header plus replay index for the largest
+// capacity that entry point accepts.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; every use of the memory goes through the address that call returns.
+static_assert(ARIDE_STATIC_MAX_REPLAY <= ARIDE_MAX_REPLAY, "the static workspace serves a legal capacity");
+constexpr size_t kScratchBytes = kHeaderBytes + replay_index_bytes(ARIDE_STATIC_MAX_REPLAY);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // address of `scratch` on each device, looked up once
+
+// Address of the current device's copy of `scratch`; nullptr when the look-up fails.
+static void* scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 }  // namespace aride
 
 using namespace aride;
@@ -216,6 +248,37 @@ int aride_sample_prioritized(const float* weights, int64_t M, void* ws, size_t w
     hipError_t err = sample_launch(weights, M, replay_ws(ws, M), uniforms, (int)K, (long long*)idx_out, prob_out,
                                    (hipStream_t)stream);
     return err == hipSuccess ? ARIDE_OK : ARIDE_E_HIP;
+}
+
+int aride_sample_prioritized_static(const float* weights, int64_t M, const double* uniforms, int64_t K,
+                                    int64_t* idx_out, float* prob_out, aride_status* status_out,
+                                    void* stream) {
+    if (K < 0 || M <= 0) return ARIDE_E_SHAPE;
+    if (M > ARIDE_STATIC_MAX_REPLAY || K > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (!weights) return ARIDE_E_NULL;
+    if (misaligned(weights, 16)) return ARIDE_E_ALIGN;
+    if (K == 0) return ARIDE_OK;
+    if (!uniforms || !idx_out) return ARIDE_E_NULL;
+    if (misaligned(uniforms, 8) || misaligned(idx_out, 8) || (status_out && misaligned(status_out, 8)))
+        return ARIDE_E_ALIGN;
+    void* ws = scratch_of_current_device();
+    if (!ws) return ARIDE_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    // The array keeps what the last call left: the status block starts from zero on every call (a
+    // fill kernel, not a memset node, so that the call may be recorded into a graph); the index
+    // arrays are all written by the rebuild before anything reads them.
+    hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(64), 0, st, (unsigned long long*)ws, kHeaderBytes / 8);
+    if (hipGetLastError() != hipSuccess) return ARIDE_E_HIP;
+    const ReplayWs w = replay_ws(ws, M);
+    if (update_launch(const_cast<float*>(weights), M, nullptr, nullptr, 0, 0.f, w, st) != hipSuccess)
+        return ARIDE_E_HIP;   // K = 0: no weight is written
+    if (sample_launch(weights, M, w, uniforms, (int)K, (long long*)idx_out, prob_out, st) != hipSuccess)
+        return ARIDE_E_HIP;
+    if (status_out) {
+        hipLaunchKernelGGL(k_copy_status, dim3(1), dim3(64), 0, st, w.hdr, reinterpret_cast<WsHeader*>(status_out));
+        if (hipGetLastError() != hipSuccess) return ARIDE_E_HIP;
+    }
+    return ARIDE_OK;
 }
 
 int aride_actor_loss_grad(const void* logits_bf16, int64_t R, int64_t V, int64_t row_stride,

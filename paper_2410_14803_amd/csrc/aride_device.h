@@ -67,9 +67,9 @@ struct ReplayWs {
     unsigned long long* sub_sum;
     unsigned long long* coarse_cum;
 };
-inline size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
-inline size_t replay_blocks(long long M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
-inline size_t replay_index_bytes(long long M) {
+constexpr size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
+constexpr size_t replay_blocks(long long M) { return (size_t)((M + kReplayBlock - 1) / kReplayBlock); }
+constexpr size_t replay_index_bytes(long long M) {
     if (M <= 0) return 0;
     const size_t nblk = replay_blocks(M);
     return kSuperBytes + kPartBytes + round_up_256(nblk * 8) + kSuperBytes + kChunkBytes + kQuarterBytes + kTouchedBytes + kCoarseBytes +

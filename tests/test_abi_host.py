@@ -152,3 +152,21 @@ def test_replay_rejects_bad_arguments(L):
     assert L.aride_workspace_init(None, 256, None) == b.E_WORKSPACE
     assert L.aride_workspace_init(ws, 100, None) == b.E_WORKSPACE
     assert L.aride_status_read(None, None, None) == b.E_NULL
+
+
+def test_static_draw_rejects_bad_arguments(L):
+    # everything below is turned away before the library's static array is even looked up
+    w, a = P(4096), P(16384)
+    s = L.aride_sample_prioritized_static
+    assert s(w, 0, a, 4, a, None, None, None) == b.E_SHAPE
+    assert s(w, 1000, a, -1, a, None, None, None) == b.E_SHAPE
+    assert s(w, b.STATIC_MAX_REPLAY + 1, a, 4, a, None, None, None) == b.E_RANGE      # beyond the array's size
+    assert s(None, 1000, a, 4, a, None, None, None) == b.E_NULL
+    assert s(P(4100), 1000, a, 4, a, None, None, None) == b.E_ALIGN
+    assert s(w, 1000, None, 4, a, None, None, None) == b.E_NULL
+    assert s(w, 1000, a, 4, None, None, None, None) == b.E_NULL
+    assert s(w, 1000, P(16388), 4, a, None, None, None) == b.E_ALIGN
+    assert s(w, 1000, a, 4, a, None, P(16388), None) == b.E_ALIGN
+    assert s(w, 1000, a, 0, a, None, None, None) == b.OK
+    text = open(os.path.join(ROOT, "include", "aride.h")).read()
+    assert int(re.search(r"#define\s+ARIDE_STATIC_MAX_REPLAY\s+\(1 << (\d+)\)", text).group(1)) == 20
