@@ -51,6 +51,8 @@ extern "C" {
 #define ARIDE_ST_BAD_UNIFORM 0x10u /* a uniform < 0 or NaN was read as 0 */
 
 #define ARIDE_MAX_REPLAY (1 << 24) /* largest M: keeps the integer CDF below 2^63 */
+#define ARIDE_MAX_STEPS 2147475455LL      /* largest N of the scan calls: 2^31 - 1 - 8192 (a chunk of steps past N still indexes as int32) */
+#define ARIDE_MAX_TRAJECTORIES 33554431LL /* largest B of the scan calls: 2^25 - 1 */
 
 #define ARIDE_TRACE_RETRACE 0  /* Section 5.2: c_i = lambda * min(1, rho_i), product from i = t+1 */
 #define ARIDE_TRACE_VTRACE  1  /* the V-trace targets the paper contrasts Retrace with */
@@ -169,7 +171,8 @@ int aride_score_logits_timed(const void* logits_bf16, int64_t R, int64_t V, int6
  *  logp_pi, logp_mu, reward, value  fp32 [N];  q fp32 [N] nullable;  boot fp32 [B]
  *  nullable (0);  traj_offsets int32 [B+1] non-decreasing;  target, td, rho fp32 [N]
  *  nullable.  Empty trajectories are allowed.
- * Errors: E_NULL, E_SHAPE (B<0, N<0), E_RANGE (N > 2^31-1, unknown mode).  B == 0 is a no-op.
+ * Errors: E_NULL, E_SHAPE (B<0, N<0), E_RANGE (N > ARIDE_MAX_STEPS, B > ARIDE_MAX_TRAJECTORIES, unknown mode).
+ *         B == 0 is a no-op.
  */
 int aride_retrace_targets(const float* logp_pi, const float* logp_mu, const float* reward,
                           const float* value, const float* q, const float* boot,
@@ -200,7 +203,7 @@ int aride_mc_returns(const float* reward, const int32_t* traj_offsets, int64_t B
  *
  *  td, rho, ent fp32 [N]; traj_offsets int32 [B+1]; step_prio fp32 [N] nullable;
  *  traj_prio fp32 [B] nullable.
- * Errors: E_NULL, E_SHAPE, E_RANGE (td_scale or ent_scale == 0, N > 2^31-1).
+ * Errors: E_NULL, E_SHAPE, E_RANGE (td_scale or ent_scale == 0, N or B as above).
  */
 int aride_compute_priorities(const float* td, const float* rho, const float* ent,
                              const int32_t* traj_offsets, int64_t B, int64_t N,

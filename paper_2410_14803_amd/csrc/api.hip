@@ -139,7 +139,7 @@ static int retrace_checked(const float* logp_pi, const float* logp_mu, const flo
                            int64_t B, int64_t N, aride_retrace_cfg cfg, const aride_prio_cfg* pcfg, float* target,
                            float* td, float* rho, float* step_prio, float* traj_prio, void* stream) {
     if (B < 0 || N < 0) return ARIDE_E_SHAPE;
-    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (N > ARIDE_MAX_STEPS || B > ARIDE_MAX_TRAJECTORIES) return ARIDE_E_RANGE;
     if (pcfg && (!(pcfg->td_scale != 0.f) || !(pcfg->ent_scale != 0.f))) return ARIDE_E_RANGE;
     if (B == 0) return ARIDE_OK;
     if (!traj_offsets) return ARIDE_E_NULL;
@@ -175,7 +175,7 @@ int aride_retrace_priorities(const float* logp_pi, const float* logp_mu, const f
 int aride_mc_returns(const float* reward, const int32_t* traj_offsets, int64_t B, int64_t N, float gamma,
                      float* ret, float* label, void* stream) {
     if (B < 0 || N < 0) return ARIDE_E_SHAPE;
-    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (N > ARIDE_MAX_STEPS || B > ARIDE_MAX_TRAJECTORIES) return ARIDE_E_RANGE;
     if (B == 0) return ARIDE_OK;
     if (!traj_offsets || (N > 0 && !reward)) return ARIDE_E_NULL;
     hipError_t err = mc_returns_launch(reward, traj_offsets, (int)B, (int)N, gamma, ret, label,
@@ -187,7 +187,7 @@ int aride_compute_priorities(const float* td, const float* rho, const float* ent
                              const int32_t* traj_offsets, int64_t B, int64_t N, aride_prio_cfg cfg,
                              float* step_prio, float* traj_prio, void* stream) {
     if (B < 0 || N < 0) return ARIDE_E_SHAPE;
-    if (N > 0x7fffffffLL || B > 0x7fffffffLL / 64) return ARIDE_E_RANGE;
+    if (N > ARIDE_MAX_STEPS || B > ARIDE_MAX_TRAJECTORIES) return ARIDE_E_RANGE;
     if (!(cfg.td_scale != 0.f) || !(cfg.ent_scale != 0.f)) return ARIDE_E_RANGE;
     if (B == 0) return ARIDE_OK;
     if (!traj_offsets) return ARIDE_E_NULL;

@@ -1,232 +1,441 @@
-// retrace_targets and compute_priorities (Sections 5.2 and 5.3 of the DistRL paper).
+// retrace_targets, compute_priorities, the two in one pass, and mc_returns (Sections 5.1, 5.2 and
+// 5.3 of the DistRL paper) as ONE flat segmented scan over the flattened steps.
 //
-// Retrace(lambda): Delta_t = delta_t + gamma*lambda*min(1, rho_{t+1}) * Delta_{t+1} is an
-// affine recurrence X -> b + a*X running backwards through each trajectory, and affine maps
-// compose associatively.  One wave owns one trajectory and walks it from its end in tiles of
-// 256 steps, staged in LDS:
-//   1. coalesced: lane l loads steps end-1-(64i+l), i = 0..3 (all loads of a tile in flight
-//      together), forms delta and rho, and parks each step's map X -> b + a*X (a = gamma *
-//      lambda * min(1, rho of the NEXT step), b = delta) in LDS in reverse-time order;
-//   2. transposed: lane j takes the four consecutive maps 4j..4j+3 out of LDS, composes them
-//      serially, a 6-round shuffle scan combines the 64 lane aggregates, and the lane then
-//      replays its four maps from the value entering it; the four Delta go back to LDS;
-//   3. coalesced again: target = Q + Delta, delta and rho are stored as contiguous runs.
-// Delta and c of the tile's earliest step are carried in registers to the next tile.  The
-// coefficient in front of the trajectory's last step is 0 (nothing follows it), which is
-// what keeps trajectories apart.  HBM-bound (32 bytes per step); no contraction, no MFMA.
+// Retrace(lambda): Delta_t = delta_t + gamma*lambda*min(1, rho_{t+1}) * Delta_{t+1} is an affine
+// recurrence X -> b + a*X running backwards through each trajectory, and affine maps compose
+// associatively.  A trajectory's last step takes nothing from the step after it: its map is a
+// reset, and that is all that keeps trajectories apart.  So the scan does not follow trajectories.
+// The N steps are cut into chunks of 256 regardless of where trajectories begin and end:
+//   * a wave owns a span of consecutive chunks and walks it from the last chunk to the first.
+//     In a chunk lane l holds four consecutive steps: with 16-byte aligned arrays every load and
+//     store is one contiguous 16-byte access per lane, every lane is busy whatever the mix of
+//     lengths, no address depends on the offsets array, and all loads of a chunk go out back to
+//     back.  The scan's values at a chunk's first step stay in registers for the chunk below.
+//   * where trajectories begin and end inside a chunk is marked in the wave's own 2 KB of LDS:
+//     lane i looks at trajectory top - i, walking down from the trajectory `top` that holds the
+//     chunk's last step; the trajectory that holds the step before the chunk is the next `top`.
+//     Only a span's first `top` is searched for: one probe around the place an even spread of
+//     lengths would put it, else a 64-ary search through the offsets.
+//   * the value entering a span from the right is whatever the trajectory crossing its right end
+//     contributes: the wave scans that trajectory's remainder first (for trajectories of up to 256
+//     steps that is one chunk, whose loads go out with the span's first).  No wave ever waits for
+//     another -- there is no barrier, no atomic, nothing exchanged -- and every result is a
+//     fixed function of the inputs (the same bits on every run).
+//   * inside a chunk: each lane composes its four maps, a 6-round shuffle scan runs down the
+//     lanes, and each lane replays its four maps from the value entering it.  A reset is carried
+//     as a flag and selected, never multiplied by zero, so that an infinity or NaN in one
+//     trajectory cannot leak into its neighbour.
+// The priorities of Section 5.3 ride along (PRIO): the per-trajectory mean is a second channel of
+// the same scan, the segmented sum S_t = p_t + S_{t+1}, read off at each trajectory's first step
+// by the wave that owns that step.  The Monte-Carlo return of Section 5.1 is the map
+// X -> r_t + gamma*X; compute_priorities alone is the sum channel by itself.
+// HBM-bound (12 to 40 bytes per step); no contraction, no MFMA.
 #include "aride_device.h"
 
 namespace aride {
 
-constexpr int kTile = 256;          // steps per wave and tile
-constexpr int kPerLane = kTile / kWave;
+constexpr int kChunk = 4 * kWave;          // steps a wave scans at a time: four per lane
+constexpr int kWavesPerBlock = 4;          // independent waves in a workgroup of 256 threads
+enum { kModeRetrace = 0, kModeVtrace = 1, kModeReturns = 2, kModePriorities = 3 };
 
-// Orders this wave's LDS writes before its later LDS reads by other lanes (LDS operations of
-// one wave execute in order; this only stops the compiler from moving them).
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Steps 2 of the tile: the maps X -> b_p + a_p X of the 256 positions are in LDS (sa, sb) in
-// reverse-time order; on return sb holds Delta_p = (f_p o ... o f_0)(carry) and the function
-// value is Delta_255.
-__device__ __forceinline__ float tile_scan(float* sa, float* sb, int lane, float carry) {
-    const float4 a4 = *reinterpret_cast<const float4*>(sa + 4 * lane);
-    const float4 b4 = *reinterpret_cast<const float4*>(sb + 4 * lane);
-    float A = a4.x, Bv = b4.x;
-    Bv = fmaf(a4.y, Bv, b4.y); A *= a4.y;
-    Bv = fmaf(a4.z, Bv, b4.z); A *= a4.z;
-    Bv = fmaf(a4.w, Bv, b4.w); A *= a4.w;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {      // inclusive scan of map composition over lanes
-        const float pa = __shfl_up(A, d, kWave);
-        const float pb = __shfl_up(Bv, d, kWave);
-        if (lane >= d) { Bv = fmaf(A, pb, Bv); A = A * pa; }
-    }
-    // value entering this lane: the composition of all earlier lanes applied to the carry
-    const float ea = __shfl_up(A, 1, kWave), eb = __shfl_up(Bv, 1, kWave);
-    const float x_in = lane ? fmaf(ea, carry, eb) : carry;
-    float4 D;
-    D.x = fmaf(a4.x, x_in, b4.x);
-    D.y = fmaf(a4.y, D.x, b4.y);
-    D.z = fmaf(a4.z, D.y, b4.z);
-    D.w = fmaf(a4.w, D.z, b4.w);
-    *reinterpret_cast<float4*>(sb + 4 * lane) = D;
-    return __shfl(D.w, kWave - 1, kWave);
-}
+struct FlatArgs {
+    const float* logp_pi; const float* logp_mu; const float* reward; const float* value;
+    const float* q; const float* boot;
+    const float* td_in; const float* rho_in;      // kModePriorities: the stored TD errors and ratios
+    const int* offsets; int B; int N;
+    float gamma, lambda, rho_bar, c_bar;
+    float* target; float* td; float* rho_out;     // Retrace / V-trace outputs (nullable)
+    float* ret; float* label;                     // Monte-Carlo outputs (nullable)
+    PrioArgs pa;
+    int vec;                                      // every array is 16-byte aligned: the 16-byte-access kernels serve
+};
 
 // Section 5.3 / Appendix A.4.3: p_t = w1*|delta_t|/s_delta + w2*rho~_t + w3*H_t/s_H + eps.
-__device__ __forceinline__ float step_priority(float td, float rho, float ent, float w_td, float w_rho,
-                                               float w_ent, float inv_td_scale, float inv_ent_scale,
-                                               float eps, int truncate) {
-    const float r = truncate ? fminf(1.f, rho) : rho;
-    return w_td * fabsf(td) * inv_td_scale + w_rho * r + w_ent * ent * inv_ent_scale + eps;
+__device__ __forceinline__ float step_priority(float td, float rho, float ent, const PrioArgs& pa) {
+    const float r = pa.truncate ? fminf(1.f, rho) : rho;
+    return pa.w_td * fabsf(td) * pa.inv_td_scale + pa.w_rho * r + pa.w_ent * ent * pa.inv_ent_scale + pa.eps;
 }
 
-// VTRACE = false: Retrace(lambda) as in Section 5.2 -- the coefficient in front of Delta_{t+1}
-// is gamma*lambda*min(1, rho_{t+1}) and the additive term is delta_t.
-// VTRACE = true: the V-trace targets of IMPALA, which the paper contrasts Retrace with
-// (Section 2, Appendix A.4.1): additive term min(rho_bar, rho_t)*delta_t, coefficient
-// gamma*lambda*min(c_bar, rho_t) -- the step's OWN ratio, not its successor's.
-// PRIO = true: the priorities of Section 5.3 are formed in the same pass from the TD error and
-// the ratio the wave already holds (plus one more load per step, the entropy), and the
-// trajectory's mean priority from a wave sum: 36 bytes per step instead of the 48 the two
-// kernels move between them, and one launch instead of two.
-template <bool VTRACE, bool PRIO>
-__global__ __launch_bounds__(256) void k_retrace(
-    const float* __restrict__ logp_pi, const float* __restrict__ logp_mu,
-    const float* __restrict__ reward, const float* __restrict__ value,
-    const float* __restrict__ q, const float* __restrict__ boot,
-    const int* __restrict__ offsets, int B, int N, float gamma, float lambda, float rho_bar, float c_bar,
-    float* __restrict__ target, float* __restrict__ td, float* __restrict__ rho_out, PrioArgs pa) {
-    __shared__ __attribute__((aligned(16))) float lds_a[4][kTile];   // coefficient on Delta_{t+1}
-    __shared__ __attribute__((aligned(16))) float lds_b[4][kTile];   // additive term, later Delta
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (b >= B) return;   // whole waves leave together; there is no workgroup barrier below
-    // offsets outside [0, N] are clamped so a malformed CSR array cannot reach past the inputs
-    const int lo = max(offsets[b], 0), hi = min(offsets[b + 1], N);
-    const float boot_b = boot ? boot[b] : 0.f;
-    float* sa = lds_a[wave];
-    float* sb = lds_b[wave];
+// Orders this wave's LDS writes before its later LDS reads by other lanes (LDS operations of one
+// wave execute in order; this only stops the compiler from moving them).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
 
-    float carry_delta = 0.f;  // Delta of the step just after this tile (0 past the end)
-    float carry_c = 0.f;      // Retrace: c of that step (0 past the end: nothing follows the last step)
-    float prio_sum = 0.f;     // PRIO: this lane's share of the trajectory's priorities
-    for (int end = hi; end > lo; end -= kTile) {
-        // 1. coalesced loads; position p = 64*i + lane holds step t = end-1-p
-        float dlt[kPerLane], rho[kPerLane], qv[kPerLane], ev[kPerLane];
+// Steps t0 .. t0+3 of one array (t0 a multiple of 4, last = the array's last index >= 0).  No
+// branch and nothing that waits, so that a chunk's loads all go out back to back:
+//  VEC   (16-byte aligned arrays) one 16-byte load from the lane's own block of four or, for lanes
+//        past it, from the block that holds the last step -- an aligned block with at least one
+//        step in it, so the access stays inside memory the array's last page maps;
+//  !VEC  four 4-byte loads from indices clamped into the array.
+// Values at steps that do not exist are whatever was there; the scan never uses them.
+template <bool VEC>
+__device__ __forceinline__ float4 load4(const float* __restrict__ p, int t0, int last) {
+    if constexpr (VEC) return *reinterpret_cast<const float4*>(p + min(t0, last & ~3));
+    return make_float4(p[min(t0, last)], p[min(t0 + 1, last)], p[min(t0 + 2, last)], p[min(t0 + 3, last)]);
+}
+template <bool VEC>
+__device__ __forceinline__ void store4(float* __restrict__ p, int t0, int limit, const float (&x)[4]) {
+    if (p == nullptr) return;
+    if (VEC && t0 + 3 < limit) {                     // written once, not read again by this kernel
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 o = {x[0], x[1], x[2], x[3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p + t0));
+        return;
+    }
 #pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = end - 1 - (i * kWave + lane);
-            float d = 0.f, r = 0.f, qt = 0.f, e = 0.f;
-            if (t >= lo) {
-                const float vt = value[t];
-                qt = q ? q[t] : vt;
-                const float vnext = (t == hi - 1) ? boot_b : value[t + 1];
-                d = reward[t] + gamma * vnext - qt;
-                r = expf(logp_pi[t] - logp_mu[t]);
-                if constexpr (PRIO) e = pa.ent[t];
-            }
-            dlt[i] = d; rho[i] = r; qv[i] = qt; ev[i] = e;
+    for (int j = 0; j < 4; ++j) if (t0 + j < limit) p[t0 + j] = x[j];
+}
+
+// What a lane reads for its four steps, and for the step after them when it is the wave's last lane.
+struct LaneIn {
+    float4 lp, lm, r, v, q, ent, td, rho;
+    float lp_n, lm_n, v_n;
+};
+
+// The chunk that starts at step c0; steps at or past `limit` do not exist.
+template <int MODE, bool PRIO, bool VEC>
+__device__ __forceinline__ LaneIn load_lane(const FlatArgs& g, int c0, int limit) {
+    const int lane = threadIdx.x & 63, t0 = c0 + 4 * lane;
+    LaneIn in = {};
+    if (__builtin_amdgcn_readfirstlane(limit) <= 0) return in;      // no steps at all (and maybe no arrays)
+    const int last = limit - 1;
+    if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
+        in.lp = load4<VEC>(g.logp_pi, t0, last);
+        in.lm = load4<VEC>(g.logp_mu, t0, last);
+        in.r = load4<VEC>(g.reward, t0, last);
+        in.v = load4<VEC>(g.value, t0, last);
+        in.q = load4<VEC>(g.q ? g.q : g.value, t0, last);
+    }
+    if constexpr (MODE == kModeReturns) in.r = load4<VEC>(g.reward, t0, last);
+    if constexpr (MODE == kModePriorities) {
+        in.td = load4<VEC>(g.td_in, t0, last);
+        in.rho = load4<VEC>(g.rho_in, t0, last);
+    }
+    if constexpr (PRIO) in.ent = load4<VEC>(g.pa.ent, t0, last);
+    if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
+        if (lane == kWave - 1 && t0 + 4 < limit) {      // the next chunk's first step
+            in.v_n = g.value[t0 + 4];
+            if constexpr (MODE == kModeRetrace) { in.lp_n = g.logp_pi[t0 + 4]; in.lm_n = g.logp_mu[t0 + 4]; }
+        }
+    }
+    return in;
+}
+
+__device__ __forceinline__ float f4(const float4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = max(v, __shfl_xor(v, d, kWave));
+    return v;
+}
+
+// One chunk of 256 steps starting at step c0, scanned backwards by the wave.
+//  MAIN   a chunk of the wave's span: trajectory begins and ends come from the LDS marks, results
+//         are stored, trajectory means are written at the begins;
+//  !MAIN  a chunk of the one trajectory that runs on past the span: it ends at step `limit`-1
+//         with bootstrap value `boot_end`; nothing is stored.
+// carry[c]: value of channel c entering the chunk from the right; on return, its value at the
+// chunk's first step (the same in every lane).
+template <int MODE, bool PRIO, bool VEC, bool MAIN>
+__device__ __forceinline__ void scan_chunk(const FlatArgs& g, const LaneIn& in, int c0, int limit,
+                                           float boot_end, int* tags, const float* aux, float (&carry)[2]) {
+    constexpr int NC = (MODE == kModePriorities ? 0 : 1) + (PRIO ? 1 : 0);
+    constexpr int CS = NC - 1;                      // the sum channel, when there is one
+    static_assert(NC >= 1 && NC <= 2, "one or two channels");
+    const int lane = threadIdx.x & 63;
+    const int t0 = c0 + 4 * lane;
+
+    int tag[4];
+    float extra[4];
+    if constexpr (MAIN) {
+        const int4 tg = *reinterpret_cast<const int4*>(tags + 4 * lane);
+        const float4 ax = *reinterpret_cast<const float4*>(aux + 4 * lane);
+        tag[0] = tg.x; tag[1] = tg.y; tag[2] = tg.z; tag[3] = tg.w;
+        extra[0] = ax.x; extra[1] = ax.y; extra[2] = ax.z; extra[3] = ax.w;
+        // cleared for the next chunk's marks (written later by this same wave: LDS keeps the order)
+        *reinterpret_cast<int4*>(tags + 4 * lane) = make_int4(0, 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { tag[j] = (t0 + j == limit - 1) ? 2 : 0; extra[j] = boot_end; }
+    }
+    bool valid[4], reset[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        valid[j] = t0 + j < limit;
+        reset[j] = !valid[j] || (tag[j] & 2);      // a trajectory's last step, or no step at all
+    }
+
+    // ---- the maps X -> b + a*X of this lane's four steps, per channel
+    float a[NC][4], b[NC][4];
+    float rho[4], dlt[4], qv[4], prio[4];
+    if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rho[j] = valid[j] ? expf(f4(in.lp, j) - f4(in.lm, j)) : 0.f;
+        // the step after each of the four: the next element, the next lane's first, or what lane 63 loaded
+        float rho_n = __shfl_down(rho[0], 1, kWave), v_n = __shfl_down(in.v.x, 1, kWave);
+        if (lane == kWave - 1) {
+            v_n = in.v_n;
+            if constexpr (MODE == kModeRetrace) rho_n = (t0 + 4 < limit) ? expf(in.lp_n - in.lm_n) : 0.f;
         }
 #pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = end - 1 - (i * kWave + lane);
-            float a, bterm;
-            if constexpr (VTRACE) {
-                a = (t >= lo && t != hi - 1) ? gamma * lambda * fminf(c_bar, rho[i]) : 0.f;
-                bterm = fminf(rho_bar, rho[i]) * dlt[i];
+        for (int j = 0; j < 4; ++j) {
+            qv[j] = f4(in.q, j);                    // Q, or the value again when there is no Q
+            const float v_next = (tag[j] & 2) ? extra[j] : (j < 3 ? f4(in.v, j + 1) : v_n);
+            dlt[j] = valid[j] ? f4(in.r, j) + g.gamma * v_next - qv[j] : 0.f;
+            if constexpr (MODE == kModeVtrace) {
+                a[0][j] = g.gamma * g.lambda * fminf(g.c_bar, rho[j]);
+                b[0][j] = fminf(g.rho_bar, rho[j]) * dlt[j];
             } else {
-                const float c = (t >= lo) ? lambda * fminf(1.f, rho[i]) : 0.f;
-                float c_next = __shfl_up(c, 1, kWave);      // position p-1 holds step t+1
-                if (lane == 0) c_next = carry_c;
-                carry_c = __shfl(c, kWave - 1, kWave);
-                a = gamma * c_next;
-                bterm = dlt[i];
+                const float c_next = g.lambda * fminf(1.f, j < 3 ? rho[j + 1] : rho_n);
+                a[0][j] = g.gamma * c_next;
+                b[0][j] = dlt[j];
             }
-            sa[i * kWave + lane] = a;
-            sb[i * kWave + lane] = bterm;
+            if (reset[j]) a[0][j] = 0.f;
         }
-        wave_lds_sync();
-        // 2. lane j composes positions 4j .. 4j+3, the wave scans, Delta goes back to LDS
-        carry_delta = tile_scan(sa, sb, lane, carry_delta);
-        wave_lds_sync();
-        // 3. coalesced stores
+    }
+    if constexpr (MODE == kModeReturns) {
 #pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = end - 1 - (i * kWave + lane);
-            if (t >= lo) {
-                if (target) target[t] = qv[i] + sb[i * kWave + lane];
-                if (td) td[t] = dlt[i];
-                if (rho_out) rho_out[t] = rho[i];
-                if constexpr (PRIO) {
-                    const float p = step_priority(dlt[i], rho[i], ev[i], pa.w_td, pa.w_rho, pa.w_ent,
-                                                  pa.inv_td_scale, pa.inv_ent_scale, pa.eps, pa.truncate);
-                    if (pa.step_prio) pa.step_prio[t] = p;
-                    prio_sum += p;
+        for (int j = 0; j < 4; ++j) { a[0][j] = reset[j] ? 0.f : g.gamma; b[0][j] = valid[j] ? f4(in.r, j) : 0.f; }
+    }
+    if constexpr (MODE == kModePriorities) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { dlt[j] = f4(in.td, j); rho[j] = f4(in.rho, j); }
+    }
+    if constexpr (PRIO) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            prio[j] = valid[j] ? step_priority(dlt[j], rho[j], f4(in.ent, j), g.pa) : 0.f;
+            a[CS][j] = reset[j] ? 0.f : 1.f;
+            b[CS][j] = prio[j];
+        }
+    }
+
+    // what does not depend on the scan goes out before it (and frees its registers)
+    if constexpr (MAIN) {
+        if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
+            store4<VEC>(g.td, t0, limit, dlt);
+            store4<VEC>(g.rho_out, t0, limit, rho);
+        }
+        if constexpr (PRIO) store4<VEC>(g.pa.step_prio, t0, limit, prio);
+    }
+
+    // ---- this lane's four maps composed: X entering at step 3 -> value at step 0
+    float A[NC], Bv[NC];
+    bool F = reset[3];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) { A[c] = a[c][3]; Bv[c] = b[c][3]; }
+#pragma unroll
+    for (int j = 2; j >= 0; --j) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            Bv[c] = reset[j] ? b[c][j] : fmaf(a[c][j], Bv[c], b[c][j]);
+            A[c] = reset[j] ? 0.f : a[c][j] * A[c];
+        }
+        F = F || reset[j];
+    }
+    // ---- suffix scan down the lanes: lane l ends with the composition of lanes l .. 63
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        float pa[NC], pb[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) { pa[c] = __shfl_down(A[c], d, kWave); pb[c] = __shfl_down(Bv[c], d, kWave); }
+        const int pf = __shfl_down((int)F, d, kWave);
+        if (lane + d < kWave && !F) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) { Bv[c] = fmaf(A[c], pb[c], Bv[c]); A[c] = A[c] * pa[c]; }
+            F = pf != 0;
+        }
+    }
+    // what lanes l+1 .. 63 make of the value entering the chunk; lane 0 holds the whole chunk's composition
+    const int gf = __shfl_down((int)F, 1, kWave);
+    const bool f0 = __shfl((int)F, 0, kWave) != 0;
+    float val[NC][4];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const float ga = __shfl_down(A[c], 1, kWave), gb = __shfl_down(Bv[c], 1, kWave);
+        const float a0 = __shfl(A[c], 0, kWave), b0 = __shfl(Bv[c], 0, kWave);
+        // ---- replay the four maps from the value entering this lane
+        float x = (lane == kWave - 1) ? carry[c] : (gf ? gb : fmaf(ga, carry[c], gb));
+#pragma unroll
+        for (int j = 3; j >= 0; --j) {
+            x = reset[j] ? b[c][j] : fmaf(a[c][j], x, b[c][j]);
+            val[c][j] = x;
+        }
+        carry[c] = f0 ? b0 : fmaf(a0, carry[c], b0);
+    }
+
+    if constexpr (MAIN) {
+        if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
+            float tg[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tg[j] = qv[j] + val[0][j];
+            store4<VEC>(g.target, t0, limit, tg);
+        }
+        if constexpr (MODE == kModeReturns) {
+            float lb[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lb[j] = val[0][j] > 0.f ? 1.f : 0.f;
+            store4<VEC>(g.ret, t0, limit, val[0]);
+            store4<VEC>(g.label, t0, limit, lb);
+        }
+        if constexpr (PRIO) {
+            if (g.pa.traj_prio) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if ((tag[j] & 1) && valid[j]) {    // a trajectory begins here: its mean
+                        const int len = (tag[j] & 2) ? 1 : __float_as_int(extra[j]);
+                        g.pa.traj_prio[tag[j] >> 2] = val[CS][j] / (float)len;
+                    }
                 }
             }
         }
-        wave_lds_sync();   // the next tile overwrites the staging area
-    }
-    if constexpr (PRIO) {
-        prio_sum = wave_sum(prio_sum);   // fixed order: reproducible
-        if (pa.traj_prio && lane == 0) pa.traj_prio[b] = hi > lo ? prio_sum / (float)(hi - lo) : 0.f;
     }
 }
 
-// Section 5.1 (state-value estimation): the Monte-Carlo return G_t = sum_{k>=t} gamma^(k-t) r_k
-// of each trajectory and the label 1[G_t > 0] the value network is trained on.  The same
-// tile scan with the map X -> r_t + gamma X (coefficient 0 in front of the last step).
-__global__ __launch_bounds__(256) void k_mc_returns(
-    const float* __restrict__ reward, const int* __restrict__ offsets, int B, int N, float gamma,
-    float* __restrict__ ret, float* __restrict__ label) {
-    __shared__ __attribute__((aligned(16))) float lds_a[4][kTile];
-    __shared__ __attribute__((aligned(16))) float lds_b[4][kTile];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (b >= B) return;
-    const int lo = max(offsets[b], 0), hi = min(offsets[b + 1], N);
-    float* sa = lds_a[wave];
-    float* sb = lds_b[wave];
-    float carry = 0.f;
-    for (int end = hi; end > lo; end -= kTile) {
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = end - 1 - (i * kWave + lane);
-            sa[i * kWave + lane] = (t >= lo && t != hi - 1) ? gamma : 0.f;
-            sb[i * kWave + lane] = (t >= lo) ? reward[t] : 0.f;
+// Each wave owns `span` consecutive chunks and walks them from the last to the first.
+template <int MODE, bool PRIO, bool VEC>
+__global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const FlatArgs g, const int span) {
+    __shared__ __attribute__((aligned(16))) int tags_all[kWavesPerBlock * kChunk];
+    __shared__ __attribute__((aligned(16))) float aux_all[kWavesPerBlock * kChunk];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int N = g.N, B = g.B;
+    // the grid is the number of spans rounded up to whole workgroups and to a multiple of 8
+    // workgroups; XCD x takes the x-th eighth
+    const long long nchunks = N > 0 ? ((long long)N + kChunk - 1) / kChunk : 1;
+    const long long c_first = (xcd_contiguous_block() * kWavesPerBlock + wave) * span;
+    if (c_first >= nchunks) return;                   // whole waves leave; there is no workgroup barrier below
+    const long long c_last = min(c_first + span, nchunks) - 1;
+    int* tags = tags_all + wave * kChunk;
+    float* aux = aux_all + wave * kChunk;
+    const int span_end = (int)min((c_last + 1) * kChunk, (long long)N);     // the span's steps end here
+
+    // ---- the trajectory that holds the span's last step.  The span that reaches N starts its walk
+    // at the last trajectory (so that it meets the empty ones recorded at N); any other looks for
+    // the smallest b with offsets[b+1] >= span_end.  offsets[B] = N >= span_end, so there is one.
+    const bool at_end = span_end >= N;
+    int top = B - 1;
+    if (!at_end) {
+        int lo = 0, n = B;
+        // First a guess: were all trajectories equally long, step span_end would lie in trajectory
+        // span_end * B / N.  One probe of the 64 trajectories around it settles the search whenever
+        // the lengths are not too unevenly spread (one round trip to memory instead of two or three).
+        {
+            const int guess = (int)((long long)span_end * B / N);
+            const int w0 = max(min(guess - 32, B - kWave), 0);          // window [w0, w0 + 64) inside [0, B)
+            const int p = min(w0 + lane, B - 1);
+            const unsigned long long m = __ballot(g.offsets[p + 1] >= span_end);
+            // the answer is inside the window when its first trajectory fails the test (or is
+            // trajectory 0) and some later one passes
+            if (m != 0ull && (!(m & 1ull) || w0 == 0)) { lo = w0 + __ffsll((long long)m) - 1; n = 1; }
         }
-        wave_lds_sync();
-        carry = tile_scan(sa, sb, lane, carry);
-        wave_lds_sync();
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = end - 1 - (i * kWave + lane);
-            if (t >= lo) {
-                const float g = sb[i * kWave + lane];
-                if (ret) ret[t] = g;
-                if (label) label[t] = g > 0.f ? 1.f : 0.f;
+        // Else a 64-ary search: each round keeps the sixty-fourth of the candidates [lo, lo+n) that holds it.
+        while (n > 1) {
+            const int stride = (n + kWave - 1) >> 6;
+            const int p = (int)min((long long)lo + (long long)(lane + 1) * stride - 1, (long long)lo + n - 1);
+            const unsigned long long m = __ballot(g.offsets[p + 1] >= span_end);
+            const int f = m ? __ffsll((long long)m) - 1 : kWave - 1;   // non-decreasing offsets: false .. false true .. true
+            const int nlo = (int)min((long long)lo + (long long)f * stride, (long long)lo + n - 1);
+            const int nhi = (int)min((long long)lo + (long long)(f + 1) * stride, (long long)lo + n);
+            n = max(nhi - nlo, 1);
+            lo = nlo;
+        }
+        top = lo;
+    }
+    // the span's last chunk, and the chunk after the span in case a trajectory runs on into it
+    LaneIn cur = load_lane<MODE, PRIO, VEC>(g, (int)(c_last * kChunk), N);
+    LaneIn far;
+    if (!at_end) far = load_lane<MODE, PRIO, VEC>(g, span_end, N);
+    *reinterpret_cast<int4*>(tags + 4 * lane) = make_int4(0, 0, 0, 0);
+    wave_lds_sync();
+    float carry[2] = {0.f, 0.f};
+    // ---- a trajectory that runs on past the span is scanned first, from its end down to the span
+    if (!at_end) {
+        const int o0 = g.offsets[top], o1 = min(g.offsets[top + 1], N);
+        if (o0 < span_end && o1 > span_end) {
+            const float boot_end = g.boot ? g.boot[top] : 0.f;
+            const int nfar = (int)(((long long)o1 - span_end + kChunk - 1) / kChunk);
+            for (int m = nfar - 1; m >= 0; --m) {
+                const int c0 = (int)((long long)span_end + (long long)m * kChunk);   // span_end is a multiple of 256 here
+                if (nfar > 1) far = load_lane<MODE, PRIO, VEC>(g, c0, o1);           // else: loaded above already
+                scan_chunk<MODE, PRIO, VEC, false>(g, far, c0, o1, boot_end, tags, aux, carry);
             }
         }
+    }
+    for (long long c = c_last; c >= c_first; --c) {
+        const int c0 = (int)(c * kChunk);
+        const int c_end = (int)min((long long)c0 + kChunk, (long long)N);
+        if (c != c_last) cur = load_lane<MODE, PRIO, VEC>(g, c0, N);
+        // ---- mark the begins and ends of the trajectories that touch the chunk, walking down from
+        // `top`: lane i takes trajectory top - i, top - i - 64, .. until one lies wholly below the
+        // chunk.  A mark is (trajectory << 2) | 1 at a first step | 2 at a last step; beside it the
+        // bootstrap value (at an end) or the length (at a begin that is not also the end).
+        int below = -1;                               // the trajectory that holds step c0 - 1
+        for (int b = top - lane; b >= 0; b -= kWave) {
+            const int o0 = g.offsets[b], o1 = g.offsets[b + 1];
+            const bool empty = o1 <= o0;
+            if (!empty && o0 < c0 && c0 <= o1) below = b;
+            if (o1 < c0 || (o1 == c0 && !empty)) break;        // wholly below the chunk, and so are all before it
+            if (empty) {                              // mean priority 0, written by the chunk that owns position o0
+                if constexpr (PRIO) {
+                    if (g.pa.traj_prio && ((o0 >= c0 && o0 < c_end) || (o0 >= N && c_end >= N))) g.pa.traj_prio[b] = 0.f;
+                }
+            } else {
+                const float bt = g.boot ? g.boot[b] : 0.f;
+                const int ps = o0 - c0, pe = o1 - 1 - c0;
+                if (ps == pe) {
+                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 3; aux[ps] = bt; }
+                } else {
+                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 1; aux[ps] = __int_as_float(o1 - o0); }
+                    if (pe >= 0 && pe < kChunk) { tags[pe] = (b << 2) | 2; aux[pe] = bt; }
+                }
+            }
+        }
+        below = wave_max_i32(below);
         wave_lds_sync();
+        scan_chunk<MODE, PRIO, VEC, true>(g, cur, c0, N, 0.f, tags, aux, carry);
+        top = below;
     }
 }
 
-// Section 5.3 / Appendix A.4.3: p_t = w1*|delta_t|/s_delta + w2*rho~_t + w3*H_t/s_H + eps and
-// the per-trajectory mean.  One wave per trajectory, 256 steps per round with all loads of a
-// round in flight together, fixed-order butterfly sum so results are reproducible.
-__global__ __launch_bounds__(256) void k_priorities(
-    const float* __restrict__ td, const float* __restrict__ rho, const float* __restrict__ ent,
-    const int* __restrict__ offsets, int B, int N, float w_td, float w_rho, float w_ent,
-    float inv_td_scale, float inv_ent_scale, float eps, int truncate,
-    float* __restrict__ step_prio, float* __restrict__ traj_prio) {
-    const int lane = threadIdx.x & 63;
-    const int b = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (b >= B) return;
-    const int lo = max(offsets[b], 0), hi = min(offsets[b + 1], N);
-    float acc = 0.f;
-    for (int t0 = lo; t0 < hi; t0 += kTile) {
-        float p[kPerLane];
+// compute_priorities without a per-trajectory output: the step priorities alone, no trajectory
+// structure is looked at; a chunk per wave.
+template <bool VEC>
+__global__ __launch_bounds__(kWave * kWavesPerBlock) void k_step_priorities(const FlatArgs g) {
+    const int N = g.N;
+    const long long chunk = xcd_contiguous_block() * kWavesPerBlock + (threadIdx.x >> 6);
+    if (chunk * kChunk >= N) return;
+    const int c0 = (int)(chunk * kChunk), t0 = c0 + 4 * (int)(threadIdx.x & 63);
+    const LaneIn in = load_lane<kModePriorities, true, VEC>(g, c0, N);
+    float prio[4];
 #pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = t0 + i * kWave + lane;
-            p[i] = 0.f;
-            if (t < hi)
-                p[i] = step_priority(td[t], rho[t], ent[t], w_td, w_rho, w_ent, inv_td_scale, inv_ent_scale, eps,
-                                     truncate);
-        }
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int t = t0 + i * kWave + lane;
-            if (t < hi) { if (step_prio) step_prio[t] = p[i]; acc += p[i]; }
-        }
-    }
-    acc = wave_sum(acc);
-    if (traj_prio && lane == 0) traj_prio[b] = hi > lo ? acc / (float)(hi - lo) : 0.f;
+    for (int j = 0; j < 4; ++j) prio[j] = step_priority(f4(in.td, j), f4(in.rho, j), f4(in.ent, j), g.pa);
+    store4<VEC>(g.pa.step_prio, t0, N, prio);
+}
+
+// Chunks per wave: about 3000 waves whatever the batch (measured on 0.66 M to 84 M steps: with
+// fewer the chip is not full, with many more the spans get short and a wave's search and its look
+// past its span's end stop being a small part of its work), a chunk per wave for small batches.
+constexpr long long kTargetWaves = 3072, kMaxSpan = 256;
+
+template <int MODE, bool PRIO>
+static hipError_t flat_launch(const FlatArgs& g, hipStream_t st) {
+    const long long nchunks = g.N > 0 ? ((long long)g.N + kChunk - 1) / kChunk : 1;
+    long long span = (nchunks + kTargetWaves - 1) / kTargetWaves;
+    if (span > kMaxSpan) span = kMaxSpan;
+    const long long nwaves = (nchunks + span - 1) / span;
+    const dim3 grid(round_up_8((unsigned)((nwaves + kWavesPerBlock - 1) / kWavesPerBlock)));
+    const dim3 block(kWave * kWavesPerBlock);
+    if (g.vec) hipLaunchKernelGGL((k_flat_scan<MODE, PRIO, true>), grid, block, 0, st, g, (int)span);
+    else hipLaunchKernelGGL((k_flat_scan<MODE, PRIO, false>), grid, block, 0, st, g, (int)span);
+    return hipGetLastError();
+}
+
+static int all_aligned16(std::initializer_list<const void*> ps) {
+    for (const void* p : ps) if (p && ((uintptr_t)p & 15)) return 0;
+    return 1;
 }
 
 // pa == nullptr: targets only; otherwise the priorities are formed in the same pass.
@@ -234,32 +443,39 @@ hipError_t retrace_launch(const float* lp, const float* lm, const float* r, cons
                           const float* q, const float* boot, const int* off, int B, int N, float gamma,
                           float lambda, int vtrace, float rho_bar, float c_bar, float* target, float* td,
                           float* rho, const PrioArgs* pa, hipStream_t st) {
-    const unsigned blocks = (unsigned)(((long long)B * kWave + 255) / 256);
-    const PrioArgs none = {nullptr, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, nullptr, nullptr};
-    auto go = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, st, lp, lm, r, v, q, boot, off, B, N, gamma, lambda,
-                           rho_bar, c_bar, target, td, rho, pa ? *pa : none);
-    };
-    if (pa) { if (vtrace) go(k_retrace<true, true>); else go(k_retrace<false, true>); }
-    else    { if (vtrace) go(k_retrace<true, false>); else go(k_retrace<false, false>); }
-    return hipGetLastError();
+    FlatArgs g = {};
+    g.logp_pi = lp; g.logp_mu = lm; g.reward = r; g.value = v; g.q = q; g.boot = boot;
+    g.offsets = off; g.B = B; g.N = N;
+    g.gamma = gamma; g.lambda = lambda; g.rho_bar = rho_bar; g.c_bar = c_bar;
+    g.target = target; g.td = td; g.rho_out = rho;
+    if (pa) g.pa = *pa;
+    g.vec = all_aligned16({lp, lm, r, v, q, target, td, rho, pa ? pa->ent : nullptr, pa ? pa->step_prio : nullptr});
+    if (pa) return vtrace ? flat_launch<kModeVtrace, true>(g, st) : flat_launch<kModeRetrace, true>(g, st);
+    return vtrace ? flat_launch<kModeVtrace, false>(g, st) : flat_launch<kModeRetrace, false>(g, st);
 }
 
 hipError_t mc_returns_launch(const float* reward, const int* off, int B, int N, float gamma, float* ret,
                              float* label, hipStream_t st) {
-    const unsigned blocks = (unsigned)(((long long)B * kWave + 255) / 256);
-    hipLaunchKernelGGL(k_mc_returns, dim3(blocks), dim3(256), 0, st, reward, off, B, N, gamma, ret, label);
-    return hipGetLastError();
+    FlatArgs g = {};
+    g.reward = reward; g.offsets = off; g.B = B; g.N = N; g.gamma = gamma; g.ret = ret; g.label = label;
+    g.vec = all_aligned16({reward, ret, label});
+    return flat_launch<kModeReturns, false>(g, st);
 }
 
 hipError_t priorities_launch(const float* td, const float* rho, const float* ent, const int* off,
                              int B, int N, float w_td, float w_rho, float w_ent, float td_scale,
                              float ent_scale, float eps, int truncate, float* step_prio,
                              float* traj_prio, hipStream_t st) {
-    const unsigned blocks = (unsigned)(((long long)B * kWave + 255) / 256);
-    hipLaunchKernelGGL(k_priorities, dim3(blocks), dim3(256), 0, st, td, rho, ent, off, B, N, w_td,
-                       w_rho, w_ent, 1.f / td_scale, 1.f / ent_scale, eps, truncate, step_prio,
-                       traj_prio);
+    FlatArgs g = {};
+    g.td_in = td; g.rho_in = rho; g.offsets = off; g.B = B; g.N = N;
+    g.pa = PrioArgs{ent, w_td, w_rho, w_ent, 1.f / td_scale, 1.f / ent_scale, eps, truncate, step_prio, traj_prio};
+    g.vec = all_aligned16({td, rho, ent, step_prio});
+    if (traj_prio) return flat_launch<kModePriorities, true>(g, st);
+    if (!step_prio || N == 0) return hipSuccess;
+    const long long nchunks = ((long long)N + kChunk - 1) / kChunk;
+    const dim3 grid(round_up_8((unsigned)((nchunks + kWavesPerBlock - 1) / kWavesPerBlock)));
+    if (g.vec) hipLaunchKernelGGL(k_step_priorities<true>, grid, dim3(kWave * kWavesPerBlock), 0, st, g);
+    else hipLaunchKernelGGL(k_step_priorities<false>, grid, dim3(kWave * kWavesPerBlock), 0, st, g);
     return hipGetLastError();
 }
 

@@ -86,6 +86,8 @@ def test_retrace_and_priorities_reject_bad_arguments(L):
     assert f(a, a, a, a, None, None, a, -1, 4, cfg, a, a, a, None) == b.E_SHAPE
     assert f(a, a, a, a, None, None, a, 2, -4, cfg, a, a, a, None) == b.E_SHAPE
     assert f(a, a, a, a, None, None, a, 2, 1 << 31, cfg, a, a, a, None) == b.E_RANGE
+    assert f(a, a, a, a, None, None, a, 2, (1 << 31) - 8192, cfg, a, a, a, None) == b.E_RANGE   # ARIDE_MAX_STEPS + 1
+    assert f(a, a, a, a, None, None, a, 1 << 25, 4, cfg, a, a, a, None) == b.E_RANGE             # ARIDE_MAX_TRAJECTORIES + 1
     assert f(a, a, a, a, None, None, None, 2, 4, cfg, a, a, a, None) == b.E_NULL
     assert f(None, a, a, a, None, None, a, 2, 4, cfg, a, a, a, None) == b.E_NULL
     assert f(a, a, a, a, None, None, a, 0, 0, cfg, a, a, a, None) == b.OK

@@ -280,3 +280,144 @@ def test_one_pass_on_config3_and_nullable_outputs(oracle):
     b.retrace_priorities(lp, lm, si["reward"], si["value"], ent, off, cfg.gamma, cfg.lam, cfg.w)
     torch.cuda.synchronize()
     assert torch.equal(tp, got["traj_prio"])
+
+
+# ---- the flat scan: tiles of 768, 1792 or 3840 steps (by batch size) cut the step axis wherever they fall
+
+
+def one_pass_against_oracle(oracle, off_np, seed, gamma, lam, tag, vtrace=False, use_boot=True):
+    cfg = synth.CONFIGS[3]
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=DEV)
+    lp = synth.policy_logprobs(N, seed, DEV)
+    si = synth.step_inputs(cfg, off_np, seed + 1, DEV)
+    lm = lp + 0.2 * si["mu_noise"]
+    g = torch.Generator(device=DEV); g.manual_seed(seed + 2)
+    boot = (torch.rand(len(off_np) - 1, generator=g, device=DEV) - 0.5) if use_boot else None
+    ent = torch.rand(N, generator=g, device=DEV) * 8
+    w = (1.0, 0.5, 0.1)
+    kw = dict(td_scale=2.0, ent_scale=8.0, eps=1e-3)
+    tr = dict(vtrace=True, rho_bar=1.3, c_bar=0.9) if vtrace else {}
+    got = fused(lp, lm, si, ent, off, gamma, lam, w, q=si["q"], boot=boot, **kw, **tr)
+    okw = dict(q=npf(si["q"]), boot=None if boot is None else npf(boot))
+    args = (npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, gamma, lam)
+    want = oracle.vtrace_targets(*args, 1.3, 0.9, **okw) if vtrace else oracle.retrace_targets(*args, **okw)
+    wp = oracle.compute_priorities(want["td"], want["rho"], npf(ent), off_np, *w, **kw)
+    for k in ("target", "td", "rho"):
+        assert_close(npf(got[k]), want[k], 1.0, f"{tag} {k}")
+    assert_close(npf(got["step_prio"]), wp["step_prio"], 1.0, f"{tag} step_prio")
+    assert_close(npf(got["traj_prio"]), wp["traj_prio"], 1.0, f"{tag} traj_prio")
+    # the two calls give the same targets bit for bit and the same means to rounding
+    sep = {k: torch.full((N,), 7.0, device=DEV) for k in ("target", "td", "rho")}
+    b.retrace_targets(lp, lm, si["reward"], si["value"], off, gamma, lam, q=si["q"], boot=boot, **sep, **tr)
+    sp, tp = gpu_prio(sep["td"], sep["rho"], ent, off, w, **kw)
+    for k in ("target", "td", "rho"):
+        assert torch.equal(got[k], sep[k]), k
+    assert np.array_equal(npf(got["step_prio"]), sp)
+    assert_close(tp, wp["traj_prio"], 1.0, f"{tag} traj_prio of compute_priorities")
+    # Monte-Carlo returns ride on the same scan
+    ret = torch.full((N,), 7.0, device=DEV); lab = torch.full((N,), 7.0, device=DEV)
+    b.mc_returns(si["reward"], off, gamma, ret=ret, label=lab)
+    torch.cuda.synchronize()
+    o_ret, o_lab = oracle.mc_returns(npf(si["reward"]), off_np, gamma)
+    assert_close(npf(ret), o_ret, 1.0, f"{tag} mc return")
+    np.testing.assert_array_equal(npf(lab), o_lab)
+    return got
+
+
+@pytest.mark.parametrize("lens", [
+    [1_000_000],                                  # one trajectory, hundreds of tiles: every tile but the last looks far ahead
+    [1, 1_000_000, 1],
+    [767, 1, 768, 769, 255, 256, 257, 1, 1, 1023, 1024, 1025, 2],     # ends on, before and after the edges of 768-step tiles
+    [3839, 1, 3840, 3841, 4096, 4097, 256, 3584, 1792, 1791, 1793],
+    [0, 0, 768, 0, 0, 768, 0, 5, 0, 0],           # empty trajectories at tile edges, at the front and at the back
+    [300] * 40 + [5000] + [1] * 3000 + [257] * 9,
+])
+def test_flat_scan_tile_edges_and_long_trajectories(oracle, lens):
+    print(f"case {len(lens)} trajectories, {sum(lens)} steps", flush=True)
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    one_pass_against_oracle(oracle, off_np, 1234 + len(lens), 0.999, 1.0, "tile edges")
+    one_pass_against_oracle(oracle, off_np, 4321 + len(lens), 0.97, 0.9, "tile edges v-trace", vtrace=True, use_boot=False)
+
+
+@pytest.mark.parametrize("n_steps", [700_000, 1_200_000, 2_500_000])      # workgroups of 256, 512 and 1024 threads
+def test_flat_scan_each_workgroup_size(oracle, n_steps):
+    rng = np.random.default_rng(n_steps)
+    lens = []
+    while sum(lens) < n_steps:
+        lens += list(rng.integers(1, 600, 200)) + [int(rng.integers(3000, 20000))] + [0]
+    print(f"case {len(lens)} trajectories, {sum(lens)} steps", flush=True)
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    one_pass_against_oracle(oracle, off_np, 99, 0.99, 0.95, f"N={n_steps}")
+
+
+def test_flat_scan_keeps_trajectories_apart(oracle):
+    # an infinity, a NaN or a huge value in one trajectory stays there: the step before a
+    # trajectory's end takes nothing from the next trajectory, not even 0 * inf
+    lens = [40, 3, 900, 1, 60, 2000, 5]
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=DEV)
+    cfg = synth.CONFIGS[3]
+    lp = synth.policy_logprobs(N, 5, DEV)
+    si = synth.step_inputs(cfg, off_np, 6, DEV)
+    lm = lp + si["mu_noise"]
+    r = si["reward"].clone()
+    r[off_np[2] + 10] = float("inf")          # inside trajectory 2
+    r[off_np[4]] = float("nan")               # first step of trajectory 4
+    r[off_np[5] + 1999] = 3e38                # last step of trajectory 5
+    si2 = dict(si, reward=r)
+    ent = torch.rand(N, device=DEV)
+    got = fused(lp, lm, si2, ent, off, 0.99, 1.0, (1.0, 0.5, 0.1))
+    want = oracle.retrace_targets(npf(lp), npf(lm), npf(r), npf(si["value"]), off_np, 0.99, 1.0)
+    tg = npf(got["target"])
+    clean = np.ones(N, bool)
+    for bad in (2, 4, 5):
+        clean[off_np[bad]:off_np[bad + 1]] = False
+    assert np.all(np.isfinite(tg[clean]))
+    assert_close(tg[clean], want["target"][clean], 1.0, "clean trajectories")
+    assert np.isinf(tg[off_np[2]]) and np.isnan(tg[off_np[4]])
+    tp = npf(got["traj_prio"])
+    assert np.all(np.isfinite(tp[[0, 1, 3, 6]])) and not np.isfinite(tp[2]) and np.isnan(tp[4])
+
+
+def test_flat_scan_unaligned_arrays(oracle):
+    # arrays that do not start on a 16-byte boundary take 4-byte accesses
+    lens = [5, 900, 1, 64, 2000, 333]
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=DEV)
+    cfg = synth.CONFIGS[3]
+    shifted = lambda t: torch.cat([torch.zeros(1, device=DEV), t])[1:]      # the same values, 4 bytes off
+    lp = shifted(synth.policy_logprobs(N, 7, DEV))
+    si = {k: (shifted(v) if v.numel() == N else v) for k, v in synth.step_inputs(cfg, off_np, 8, DEV).items()}
+    assert lp.data_ptr() % 16 == 4 and lp.is_contiguous()
+    lm = lp + si["mu_noise"]
+    ent = shifted(torch.rand(N, device=DEV))
+    outs = {k: shifted(torch.full((N,), 7.0, device=DEV)) for k in ("target", "td", "rho", "step_prio")}
+    tp = torch.full((len(lens),), 7.0, device=DEV)
+    b.retrace_priorities(lp, lm, si["reward"], si["value"], ent, off, 0.99, 0.95, (1.0, 0.5, 0.1), q=si["q"],
+                         traj_prio=tp, **outs)
+    torch.cuda.synchronize()
+    want = oracle.retrace_targets(npf(lp), npf(lm), npf(si["reward"]), npf(si["value"]), off_np, 0.99, 0.95,
+                                  q=npf(si["q"]))
+    wp = oracle.compute_priorities(want["td"], want["rho"], npf(ent), off_np, 1.0, 0.5, 0.1)
+    for k in ("target", "td", "rho"):
+        assert_close(npf(outs[k]), want[k], 1.0, f"unaligned {k}")
+    assert_close(npf(outs["step_prio"]), wp["step_prio"], 1.0, "unaligned step_prio")
+    assert_close(npf(tp), wp["traj_prio"], 1.0, "unaligned traj_prio")
+
+
+def test_scan_results_are_the_same_bits_on_every_run():
+    cfg = synth.scaled(synth.CONFIGS[3], B=3000)
+    off_np = synth.trajectory_offsets(cfg, 77)
+    N = int(off_np[-1])
+    off = torch.as_tensor(off_np, device=DEV)
+    lp = synth.policy_logprobs(N, 78, DEV)
+    si = synth.step_inputs(cfg, off_np, 79, DEV)
+    lm = lp + si["mu_noise"]
+    ent = torch.rand(N, device=DEV)
+    a = fused(lp, lm, si, ent, off, cfg.gamma, cfg.lam, cfg.w)
+    c = fused(lp, lm, si, ent, off, cfg.gamma, cfg.lam, cfg.w)
+    for k in a:
+        assert torch.equal(a[k].view(torch.int32), c[k].view(torch.int32)), k
