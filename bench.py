@@ -5,8 +5,8 @@ One "step" is one pass of the whole hot path over one learner batch (the "learne
 workload: 256 trajectories of 1..20 steps, 32 action tokens per step, V = 32128 bf16
 logits; replay buffer of 65536 entries, 1024 draws):
 
-    score_logits -> retrace_targets -> compute_priorities -> sample_prioritized
-                 -> update_priorities (scatter + index rebuild)
+    score_logits -> retrace_priorities (retrace_targets and compute_priorities in one pass)
+                 -> sample_prioritized -> update_priorities (scatter + index rebuild)
 
 All inputs are synthetic, seeded, and resident in HBM before the timed region starts.
 Prints ONE JSON line: whole-job trajectory-steps/s, the HBM roofline of the dominant
@@ -98,6 +98,16 @@ def _actor_traffic(args, R):
     return TRAFFIC_ACTOR["bytes_per_launch"] if ok else None
 
 
+def _sweep_kernel_name(V):
+    """The kernel aride_score_logits dispatches for rows of V logits (the rule of score_logits_launch:
+    16-byte vectors per row from which a row is shared by 4, 8, 16 waves)."""
+    nvec = V >> 3
+    for waves, least in ((16, 12288), (8, 3072), (4, 1024)):
+        if nvec >= least:
+            return f"k_score_rows_split ({waves} waves per row at this row length)"
+    return "k_score_rows (one wave per row at this row length)"
+
+
 def _timed(torch, fn, steps, warmup):
     for _ in range(warmup):
         fn()
@@ -113,7 +123,8 @@ def _timed(torch, fn, steps, warmup):
 
 
 def bench_retrace(args, b, torch, synth, dev):
-    """One step = retrace_targets + compute_priorities over the long-scan batch (config 3)."""
+    """One step = retrace_targets + compute_priorities over the long-scan batch (config 3), as the one call
+    aride_retrace_priorities unless --two-calls."""
     cfg = synth.CONFIGS[3]
     if args.batch_scale != 1:                 # the same length mix, more trajectories
         cfg = synth.scaled(cfg, B=cfg.B * args.batch_scale)
@@ -168,8 +179,8 @@ def bench_retrace(args, b, torch, synth, dev):
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "trajectories": cfg.B, "traj_steps": N,
                    "gamma": cfg.gamma, "lambda": cfg.lam, "one_pass": bool(args.one_pass)},
-        "roofline": {"bound": "hbm", "kernel": "k_retrace with the priorities in the same pass (one launch; launch-latency bound)"
-                     if args.one_pass else "k_retrace + k_priorities (two launches; launch-latency bound)",
+        "roofline": {"bound": "hbm", "kernel": "k_flat_scan<Retrace, with priorities> (one launch)"
+                     if args.one_pass else "k_flat_scan<Retrace> + k_flat_scan<priorities> (two launches)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
@@ -305,9 +316,15 @@ def main():
                          "retrace: retrace_targets + compute_priorities on the long-scan workload (config 3). "
                          "replay: sample + update + index rebuild on the 2^24-entry buffer (config 4). "
                          "insert: circular insert of 65 536 entries into that buffer, index patched")
-    ap.add_argument("--one-pass", action="store_true",
-                    help="with --path scoring or retrace: retrace_targets and compute_priorities as the one call "
-                         "aride_retrace_priorities (one launch, TD errors and ratios not read back)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="with --path scoring or retrace: aride_retrace_targets and aride_compute_priorities as two "
+                         "calls instead of the one call aride_retrace_priorities (one launch, TD errors and "
+                         "ratios not read back), which is the default")
+    ap.add_argument("--prewarm", type=int, default=60,
+                    help="with --path scoring: untimed launches of the logit sweep before the warm-up steps. A "
+                         "process's first sustained load makes the chip's power management drop the shader clock "
+                         "from 2.4 to about 1.3 GHz within 3 ms and let it back up to its sustained 1.8 GHz over "
+                         "the next 20 ms; launches in that window take up to 40 percent longer")
     ap.add_argument("--rebuild-every-insert", action="store_true",
                     help="with --path insert: follow every insert by a full index rebuild (the comparison)")
     ap.add_argument("--rotate", type=int, default=0,
@@ -319,6 +336,7 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()
+    args.one_pass = not args.two_calls
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
@@ -391,6 +409,17 @@ def main():
         b.sample_prioritized(weights, uni[i], ws, idx, prob)
         b.update_priorities(weights, idx, step_prio[prio_src] if N < K else step_prio[:K], cfg.alpha, ws)
 
+    # Pre-warm: the sweep alone, each launch timed like the timed steps below, so that the line can
+    # show what the first window of a process costs beside the steady state (see --prewarm).
+    pre = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.prewarm)]
+    for a, c in pre:
+        a.record(); c.record()
+    torch.cuda.synchronize()
+    for i, ev in enumerate(pre):
+        b.score_logits(logits_ring[i % copies], tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
+                       step_logp=step_logp, step_ent=step_ent, sweep_events=ev)
+    torch.cuda.synchronize()
+    pre_ms = [a.elapsed_time(c) for a, c in pre]
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
@@ -446,9 +475,12 @@ def main():
                    "action_tokens": cfg.A, "vocab": cfg.V, "logit_rows": R, "logit_bytes": R * cfg.V * 2,
                    "replay_entries": M, "draws": K, "gamma": cfg.gamma, "lambda": cfg.lam, "alpha": cfg.alpha,
                    "logit_copies_in_rotation": copies, "one_pass": bool(args.one_pass)},
-        "roofline": {"bound": "hbm", "kernel": "k_score_rows_split (8 waves per row at this row length)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": _sweep_kernel_name(cfg.V), "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms},
+                     "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": sweep_ms,
+                     "prewarm_launches": args.prewarm,
+                     "ms_per_launch_first_window": (sum(pre_ms[:40]) / len(pre_ms[:40])) if pre_ms else None,
+                     "ms_per_launch_slowest_of_first_window": max(pre_ms[:40]) if pre_ms else None},
     }
 
     if not args.no_cpu_baseline:
