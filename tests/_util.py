@@ -1,12 +1,12 @@
 """Shared helpers for the parity tests: tolerances and tensor plumbing.
 
-Tolerances (fp32 accumulation against the fp64 oracle):
-  log-probabilities, Retrace targets, TD errors, ratios, priorities:
-      |g - o| <= 1e-4 * max(|o|, 1)
-  entropies:
-      |g - o| <= 1e-4 * max(|o|, 1e-2 * log V)
-The floors exist because a relative bound is meaningless next to zero (a peaked row's
-entropy, a target that happens to cancel); they are the only slack beyond 1e-4 relative.
+Tolerances (fp32 accumulation against the fp64 oracle): 1e-4 relative, with a floor of one
+hundredth of the scale of the quantity's operands,
+      |g - o| <= 1e-4 * max(|o|, 1e-2 * scale)
+scale = 1 for log-probabilities, Retrace targets, TD errors, ratios and priorities (values,
+rewards and ratios of order one), scale = log V for entropies.  The floor exists because a
+relative bound is meaningless next to zero (a peaked row's entropy, a TD error or target whose
+terms cancel): there the result is held to 1e-6 of the size of what was added up.
 Indices are compared bit for bit.
 """
 import functools
@@ -19,7 +19,19 @@ import torch
 RTOL = 1e-4
 
 
-def assert_close(got, want, floor=1.0, what="", rtol=RTOL):
+FLOOR_FRACTION = 1e-2
+
+
+# For results at the end of a chain in which each side consumed its own intermediates: a ratio
+# rho = exp(log pi - log mu) inherits the absolute error of log pi (one fp32 ulp at |log pi| ~ 500
+# is 3e-5, still inside 1e-4 relative), and a target inherits that relative error times the size
+# of the correction it sums, however small the target itself comes out.  There the floor is the
+# operand scale itself.
+CHAINED = dict(floor_fraction=1.0)
+
+
+def assert_close(got, want, scale=1.0, what="", rtol=RTOL, floor_fraction=FLOOR_FRACTION):
+    """scale: a number, or an array shaped like `want` (the size of what each element added up)."""
     g = np.asarray(got, dtype=np.float64)
     o = np.asarray(want, dtype=np.float64)
     assert g.shape == o.shape, f"{what}: shape {g.shape} vs {o.shape}"
@@ -28,17 +40,19 @@ def assert_close(got, want, floor=1.0, what="", rtol=RTOL):
     assert np.all(np.isfinite(g) == np.isfinite(o)), f"{what}: finiteness differs"
     fin = np.isfinite(o)
     np.testing.assert_array_equal(g[~fin], o[~fin], err_msg=f"{what}: non-finite values differ")
+    floor = np.broadcast_to(floor_fraction * np.asarray(scale, dtype=np.float64), o.shape)[fin]
     err = np.abs(g[fin] - o[fin])
-    bound = rtol * np.maximum(np.abs(o[fin]), floor)
-    worst = float(np.max(err / np.maximum(np.abs(o[fin]), floor))) if err.size else 0.0
-    bad = err > bound
+    denom = np.maximum(np.abs(o[fin]), floor)
+    worst = float(np.max(err / np.maximum(denom, 1e-300))) if err.size else 0.0
+    bad = err > rtol * denom
     assert not bad.any(), (f"{what}: {int(bad.sum())} of {err.size} outside 1e-4 relative "
-                           f"(floor {floor}); worst scaled error {worst:.3e}")
+                           f"(floor {float(np.min(floor)):.3g}..{float(np.max(floor)):.3g}); worst scaled error {worst:.3e}")
     return worst
 
 
 def ent_floor(V):
-    return 1e-2 * math.log(V)
+    """The scale of an entropy over V outcomes (assert_close puts the floor at a hundredth of it)."""
+    return math.log(V)
 
 
 def bits_of(logits_bf16: torch.Tensor) -> np.ndarray:
@@ -96,3 +110,36 @@ def scored_config(ci: int):
     want = oracle_score_streamed(oracle, logits, tokens, cfg.A)
     return dict(cfg=cfg, seed=seed, off_np=off_np, N=N, R=R, logits=logits, tokens=tokens, ws=ws, got=got,
                 flags=st.flags, want=want)
+
+
+GRAD_ULPS = 16 * 2.0 ** -24     # rounding the gradient kernel itself may add, relative to an element's factors
+
+
+def grad_bound(logits_bits, tokens, V, coef, beta, scale, o_tok_logp, o_tok_ent, g_tok_logp, g_tok_ent):
+    """Per-element bound on |device gradient - oracle gradient| (fp32 output), from the arithmetic of
+        g[r, v] = scale * p_v * (C_r + beta * (log p_v + H_r))           (v != token)
+        g[r, tok] = scale * (C_r * (p - 1) + beta * p * (log p + H_r)),   C_r = rho_t * A_t.
+    The second sweep takes log Z_r = x_tok - tok_logp[r] and H_r = tok_ent[r] from the first one, so an
+    absolute error e_r in tok_logp scales every p_v of the row by exp(-e_r) and shifts log p_v by e_r,
+    and an error h_r in tok_ent shifts H_r.  Where the factor C + beta*(log p + H) does not cancel that
+    is a relative error of the element and sits inside 1e-4*|o|; where it cancels, what is left is
+        scale * p_v * (|C_r| + beta * (|log p_v| + H_r + 1)) * (e_r + h_r + a few fp32 roundings).
+    e_r and h_r are measured here (device first sweep against the oracle's); the roundings are
+    GRAD_ULPS (exp2, the two-float log Z, one fused multiply-add per factor, coef in fp32).  The last
+    term is fp32's smallest normal number: below it the device flushes to zero.
+    Arguments are per row [R] except logits_bits [R, >=V]; returns [R, V]."""
+    x = (np.ascontiguousarray(logits_bits[:, :V]).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    tok = np.asarray(tokens)
+    live = (tok >= 0) & (tok < V)
+    rows = np.arange(x.shape[0])
+    xt = x[rows, np.where(live, tok, 0)]
+    log_z = xt - np.asarray(o_tok_logp, np.float64)
+    with np.errstate(over="ignore", invalid="ignore"):
+        logp = x - log_z[:, None]
+        p = np.exp(logp)
+    p = np.where(np.isfinite(p), p, 0.0)
+    abs_logp = np.where(np.isfinite(logp), np.abs(logp), 0.0)        # masked vocabulary entries: p = 0
+    inherited = np.abs(np.asarray(g_tok_logp, np.float64) - o_tok_logp) + np.abs(np.asarray(g_tok_ent, np.float64) - o_tok_ent)
+    factors = np.abs(coef)[:, None] + beta * (abs_logp + np.asarray(o_tok_ent, np.float64)[:, None] + 1.0)
+    extra = scale * p * factors * (inherited[:, None] + GRAD_ULPS) + 2.0 ** -126
+    return np.where(live[:, None], extra, 0.0)

@@ -7,7 +7,7 @@ import torch
 
 from paper_2410_14803_amd import binding as b
 from paper_2410_14803_amd import synth
-from _util import assert_close, bits_of, ent_floor, host_threads, npf, scored_config
+from _util import CHAINED, assert_close, bits_of, ent_floor, host_threads, npf, scored_config
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -69,13 +69,13 @@ def run_chain(oracle, cfg, full=False):
 
     assert_close(npf(step_logp), o_score["step_logp"], 1.0, "chain step_logp")
     assert_close(npf(step_ent), o_score["step_ent"], ent_floor(cfg.V), "chain step_ent")
-    assert_close(npf(target), o_rt["target"], 1.0, "chain target")
-    assert_close(npf(td), o_rt["td"], 1.0, "chain td")
-    assert_close(npf(rho), o_rt["rho"], 1.0, "chain rho")
-    assert_close(npf(step_prio), o_pr["step_prio"], 1.0, "chain step_prio")
-    assert_close(npf(traj_prio), o_pr["traj_prio"], 1.0, "chain traj_prio")
+    assert_close(npf(target), o_rt["target"], 1.0, "chain target", **CHAINED)
+    assert_close(npf(td), o_rt["td"], 1.0, "chain td", **CHAINED)
+    assert_close(npf(rho), o_rt["rho"], 1.0, "chain rho", **CHAINED)
+    assert_close(npf(step_prio), o_pr["step_prio"], 1.0, "chain step_prio", **CHAINED)
+    assert_close(npf(traj_prio), o_pr["traj_prio"], 1.0, "chain traj_prio", **CHAINED)
     oracle.update_priorities(w_host, npf(slots), o_pr["step_prio"][:K].astype(np.float32), cfg.alpha)
-    assert_close(npf(w), w_host, 1.0, "chain weights")
+    assert_close(npf(w), w_host, 1.0, "chain weights", **CHAINED)
     oi, op, _ = oracle.sample_prioritized(npf(w), npf(u))       # from the device's weight bits
     np.testing.assert_array_equal(npf(idx), oi)
     np.testing.assert_allclose(npf(prob), op.astype(np.float32), rtol=1e-6)
@@ -141,11 +141,11 @@ def test_chain_trajectory_priorities_as_the_stored_key(oracle, ci):
     torch.cuda.synchronize()
     st, rc = ws.status()
     assert rc == b.OK and st.flags == 0
-    assert_close(npf(traj_prio), o_pr["traj_prio"], 1.0, "p(tau)")
+    assert_close(npf(traj_prio), o_pr["traj_prio"], 1.0, "p(tau)", **CHAINED)
     o_cursor, o_slots = oracle.replay_insert(w_host, cursor, o_pr["traj_prio"].astype(np.float32), cfg.alpha)
     assert new_cursor == o_cursor == (cursor + cfg.B) % cfg.M
     np.testing.assert_array_equal(npf(slots), o_slots)
-    assert_close(npf(w), w_host, 1.0, "stored weights")
+    assert_close(npf(w), w_host, 1.0, "stored weights", **CHAINED)
     oi, op, _ = oracle.sample_prioritized(npf(w), npf(u))       # from the device's weight bits
     np.testing.assert_array_equal(npf(idx), oi)
     np.testing.assert_allclose(npf(prob), op.astype(np.float32), rtol=1e-6)
