@@ -154,6 +154,7 @@ def bench_retrace(args, b, torch, synth, dev):
                           rho=rho, vtrace=True, rho_bar=1.0, c_bar=1.0)
         b.mc_returns(si["reward"], off, cfg.gamma, ret=ret, label=lab)
     elapsed, ms = _timed(torch, step, args.steps, args.warmup)
+    mix = _mix_probe(torch, N, (6, 4) if args.one_pass else (5, 3), dev) if args.mix_probe else None
     alg_bytes = N * (20 + 12) + N * (12 + 4) + cfg.B * 12     # retrace: 5 in + 3 out; priorities: 3 in + 1 out
     if args.one_pass:
         alg_bytes = N * (24 + 16) + cfg.B * 12                # 6 in + 4 out: td and rho are not read back
@@ -183,8 +184,37 @@ def bench_retrace(args, b, torch, synth, dev):
                      if args.one_pass else "k_flat_scan<Retrace> + k_flat_scan<priorities> (two launches)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
+                     "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms, "stream_mix_probe": mix},
         "cpu_baseline": cpu}), flush=True)
+
+
+def _mix_probe(torch, N, shape, dev):
+    """A bare kernel with the scan's access pattern (shape = arrays read, arrays written; 16 bytes per
+    lane and array, no scan): the rate the memory system allows that mix of streams on N steps."""
+    import ctypes
+    nin, nout = shape
+    probe = ctypes.CDLL(os.path.join(ROOT, "paper_2410_14803_amd", "libaride_probe.so"))
+    probe.aride_probe_mix.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                                      ctypes.c_void_p]
+    n = N // 4 * 4
+    ins = [torch.rand(n, device=dev) for _ in range(nin)]
+    outs = [torch.empty(n, device=dev) for _ in range(nout)]
+    pin = torch.tensor([t.data_ptr() for t in ins] + [0] * (6 - nin), dtype=torch.int64, device=dev)
+    pout = torch.tensor([t.data_ptr() for t in outs] + [0] * (4 - nout), dtype=torch.int64, device=dev)
+    st = torch.cuda.current_stream().cuda_stream
+    go = lambda: probe.aride_probe_mix(pin.data_ptr(), pout.data_ptr(), nin, nout, n, st)
+    for _ in range(5):
+        assert go() == 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        go()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 20
+    gbps = n * 4 * (nin + nout) / (ms * 1e-3) / 1e9
+    return {"arrays_read": nin, "arrays_written": nout, "steps": n, "ms": ms, "GB/s": gbps, "frac": gbps / HBM_PEAK_GBPS}
 
 
 def bench_replay(args, b, torch, synth, dev):
@@ -333,6 +363,9 @@ def main():
     ap.add_argument("--batch-scale", type=int, default=1,
                     help="with --path retrace: multiply the number of trajectories (the kernels are "
                          "launch-bound at the configured size)")
+    ap.add_argument("--mix-probe", action="store_true",
+                    help="with --path retrace: also time a bare kernel that reads and writes as many fp32 arrays as "
+                         "the scan does and nothing else (the ceiling for that mix of read and write streams)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch a plain 1 GiB copy kernel a few times (calibrates hardware counters)")
     args = ap.parse_args()

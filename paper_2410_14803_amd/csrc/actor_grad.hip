@@ -13,15 +13,8 @@
 
 namespace aride {
 
-#ifndef ARIDE_ACTOR_NT_STORE
-#define ARIDE_ACTOR_NT_STORE 1  // non-temporal stores for the gradient
-#endif
-#ifndef ARIDE_ACTOR_UNROLL
-#define ARIDE_ACTOR_UNROLL 4   // 16-byte loads in flight per lane (bf16 output)
-#endif
-#ifndef ARIDE_ACTOR_UNROLL_F32
-#define ARIDE_ACTOR_UNROLL_F32 8   // 8-byte loads in flight per lane (fp32 output)
-#endif
+constexpr int kActorUnroll = 4;      // 16-byte loads in flight per lane (bf16 output)
+constexpr int kActorUnrollF32 = 8;   // 8-byte loads in flight per lane (fp32 output)
 
 constexpr float kLog2eA = 1.4426950408889634f;
 constexpr float kLn2A = 0.6931471805599453f;
@@ -136,14 +129,10 @@ __global__ __launch_bounds__(WPR == 1 ? 256 : 64 * WPR) void k_actor_grad(
             __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(gf + head) + i);
         } else {
             u32x4 o = {pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3]), pack_bf16(g[4], g[5]), pack_bf16(g[6], g[7])};
-#if ARIDE_ACTOR_NT_STORE
             __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(gb + head) + i);
-#else
-            *(reinterpret_cast<u32x4*>(gb + head) + i) = o;
-#endif
         }
     };
-    constexpr int kU = OUT_F32 ? ARIDE_ACTOR_UNROLL_F32 : ARIDE_ACTOR_UNROLL;
+    constexpr int kU = OUT_F32 ? kActorUnrollF32 : kActorUnroll;
     constexpr int kStep = WPR * kWave;               // vectors the row's waves cover per load
     int i = (WPR == 1 ? 0 : wave * kWave) + lane;
     if (live) {

@@ -103,7 +103,7 @@ static int score_logits_checked(const void* logits_bf16, int64_t R, int64_t V, i
                                 float* step_logp, float* step_ent, void* ws, size_t ws_bytes, void* stream,
                                 void* sweep_start, void* sweep_stop) {
     if (R < 0 || V <= 0 || A <= 0 || row_stride < V || R % A != 0) return ARIDE_E_SHAPE;
-    if (V > 0x7fffffffLL || R > (int64_t)1 << 40) return ARIDE_E_RANGE;
+    if (V > 0x7fffffffLL || R > ARIDE_MAX_ROWS) return ARIDE_E_RANGE;
     if (!ws || misaligned(ws, 256)) return ARIDE_E_WORKSPACE;
     if (R == 0) return ARIDE_OK;
     if (!logits_bf16 || !tokens) return ARIDE_E_NULL;
@@ -225,7 +225,7 @@ int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* 
     if (K < 0) return ARIDE_E_SHAPE;
     int rc = check_replay(weights, M, ws, ws_bytes);
     if (rc != ARIDE_OK) return rc;
-    if (cursor < 0 || cursor >= M || !(alpha >= 0.f) || K > ((int64_t)1 << 40)) return ARIDE_E_RANGE;
+    if (cursor < 0 || cursor >= M || !(alpha >= 0.f) || K > ((int64_t)1 << 38)) return ARIDE_E_RANGE;   // k_insert's grid
     if (K > 0 && !prio) return ARIDE_E_NULL;
     if (slots_out && misaligned(slots_out, 8)) return ARIDE_E_ALIGN;
     hipError_t err = insert_launch(weights, M, cursor, prio, K, alpha, (long long*)slots_out, replay_ws(ws, M),
@@ -287,7 +287,7 @@ int aride_actor_loss_grad(const void* logits_bf16, int64_t R, int64_t V, int64_t
                           const float* target, const float* baseline, const float* penalty,
                           aride_actor_cfg cfg, void* grad, float* loss, void* stream) {
     if (R < 0 || V <= 0 || A <= 0 || row_stride < V || R % A != 0) return ARIDE_E_SHAPE;
-    if (V > 0x7fffffffLL || R > (int64_t)1 << 40 || R / A > 0x7fffffffLL) return ARIDE_E_RANGE;
+    if (V > 0x7fffffffLL || R > ARIDE_MAX_ROWS || R / A > 0x7fffffffLL) return ARIDE_E_RANGE;
     if (!grad && !loss) return ARIDE_OK;
     if (R > 0) {
         if (!rho || !target || !baseline) return ARIDE_E_NULL;

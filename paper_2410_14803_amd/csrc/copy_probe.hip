@@ -1,11 +1,14 @@
-// Calibration aid for hardware-counter readings: a plain device-to-device copy whose HBM
-// traffic is known exactly (bytes read = bytes written = n).  Built into its own small
-// library (libaride_probe.so); it is not part of the scoring library or of its C ABI.
+// Calibration aids for the measurements: kernels whose HBM traffic is known exactly and that do
+// nothing else.  Built into their own small library (libaride_probe.so); they are not part of the
+// scoring library or of its C ABI.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// A plain device-to-device copy (bytes read = bytes written = n): what a hardware counter reads
+// for it gives the factor by which that counter's readings are scaled.
 __global__ __launch_bounds__(256) void k_copy_probe(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t nvec) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x)
         dst[i] = src[i];
@@ -23,25 +26,40 @@ extern "C" int aride_probe_copy(void* dst, const void* src, size_t nbytes, void*
     return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
-// Read-only companion: streams nbytes with non-temporal 16-byte loads and XORs them into one
-// word per workgroup (so the loads cannot be dropped).  Measures the read bandwidth a kernel
-// with no arithmetic to speak of reaches on this part.
-__global__ __launch_bounds__(256) void k_read_probe(const u32x4* __restrict__ src, size_t nvec, uint32_t* __restrict__ sink) {
-    uint32_t acc = 0;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {
-        u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
-        u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
-    }
-    for (; i < nvec; i += stride) { u32x4 a = __builtin_nontemporal_load(src + i); acc ^= a.x ^ a.y ^ a.z ^ a.w; }
-    if (acc == 0x9e3779b9u) sink[blockIdx.x & 255] = acc;   // practically never taken
+// The access pattern of the Retrace + priority scan with the scan taken out: NIN fp32 arrays
+// read and NOUT written, 16 bytes per lane and array, one pass, a trivial combination in between.
+// What this reaches is the ceiling the memory system sets for that mix of read and write streams
+// (a read-only sweep reaches 90 % of the HBM peak on this part, a mix of six read and four write
+// streams about 70 %).  Loads are plain, stores non-temporal, as in the scan.
+template <int NIN, int NOUT>
+__global__ __launch_bounds__(256) void k_mix_probe(const f32x4* const* __restrict__ in, f32x4* const* __restrict__ out,
+                                                   size_t nvec) {
+    // the grid is a multiple of 8; XCD x takes the x-th eighth
+    const size_t blk = (size_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const size_t i = blk * 256 + threadIdx.x;
+    if (i >= nvec) return;
+    f32x4 v[NIN];
+#pragma unroll
+    for (int k = 0; k < NIN; ++k) v[k] = in[k][i];
+    f32x4 acc = v[0];
+#pragma unroll
+    for (int k = 1; k < NIN; ++k) acc = acc * 0.5f + v[k];
+#pragma unroll
+    for (int k = 0; k < NOUT; ++k) __builtin_nontemporal_store(acc + (float)k, out[k] + i);
 }
 
-extern "C" int aride_probe_read(const void* src, size_t nbytes, void* sink256, int blocks, void* stream) {
-    if (!src || !sink256 || (nbytes & 15) || ((uintptr_t)src & 15) || blocks <= 0) return -1;
-    hipLaunchKernelGGL(k_read_probe, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                       (const u32x4*)src, nbytes / 16, (uint32_t*)sink256);
+// in / out: DEVICE arrays of 6 and 4 device pointers to fp32 arrays of n elements each (n a
+// multiple of 4, every array 16-byte aligned); nin in {3, 5, 6}, nout in {1, 3, 4}.
+extern "C" int aride_probe_mix(const void* in, void* out, int nin, int nout, size_t n, void* stream) {
+    if (!in || !out || (n & 3)) return -1;
+    const size_t nvec = n / 4;
+    if (nvec == 0) return 0;
+    const unsigned grid = (unsigned)(((nvec + 255) / 256 + 7) / 8 * 8);
+    auto ins = (const f32x4* const*)in;
+    auto outs = (f32x4* const*)out;
+    if (nin == 6 && nout == 4) hipLaunchKernelGGL((k_mix_probe<6, 4>), dim3(grid), dim3(256), 0, (hipStream_t)stream, ins, outs, nvec);
+    else if (nin == 5 && nout == 3) hipLaunchKernelGGL((k_mix_probe<5, 3>), dim3(grid), dim3(256), 0, (hipStream_t)stream, ins, outs, nvec);
+    else if (nin == 3 && nout == 1) hipLaunchKernelGGL((k_mix_probe<3, 1>), dim3(grid), dim3(256), 0, (hipStream_t)stream, ins, outs, nvec);
+    else return -1;
     return hipGetLastError() == hipSuccess ? 0 : -7;
 }

@@ -4,41 +4,37 @@
 //
 // Design for gfx950:
 //  * HBM-bound streaming reduction; nothing here is a contraction, so no MFMA.
-//  * One wave sweeps one row; each lane issues 16-byte loads (8 bf16), UNROLL of them back
-//    to back, so 4 KB per wave are in flight.  Spreading a row over 2 or 4 waves, prefetching
-//    the next batch before reducing the current one, or other workgroup sizes were measured
-//    and change nothing: the kernel runs at the rate of a pure read probe.
+//  * Who reads what: rows of 16 KB and more belong to one workgroup of 4, 8 or 16 waves
+//    (k_score_rows_split; rows from 16, 48, 192 KB), each wave reducing a contiguous share of 6
+//    to 16 KB of the row; shorter rows take one wave each, four rows to a workgroup
+//    (k_score_rows).  Both map blockIdx to rows so that each of the chip's 8 XCDs streams one
+//    contiguous eighth of the rows.  Each lane issues 16-byte non-temporal loads (8 bf16), four of
+//    them back to back, so 4 KB per wave are in flight.  On 64 KB rows: one wave per row and a
+//    plain mapping 84 % of the HBM peak, XCD-contiguous rows 86 %, 8 waves per row 87-90 %.
 //  * Every logit is read once.  Each lane keeps an online log-sum-exp state in base-2
 //    units against a lazily updated reference k (k = ref*log2e):
 //        s = sum 2^(x*log2e - k),   t = sum 2^(x*log2e - k) * (x*log2e - k)
 //    The reference only moves when a group's maximum exceeds it by more than kWindow,
 //    so the rescale branch is rarely taken; the exact running maximum is kept
-//    separately and all lanes are brought to the common reference once at the end.
+//    separately and all lanes, then all waves of a row, are brought to the common reference
+//    once at the end.
 //    Terms above the reference are rounded at ulp(x*log2e - k), so the window also bounds
 //    the relative error of the largest terms: 1.7e-7 at 4 nats (6.6e-7 at 16, at equal speed).
 //  * logp = ln2*(x_tok*log2e - K) - ln S  and  H = ln S - ln2*T/S  hold for any common
 //    reference K, so rounding in K cancels; and because x*log2e - k is one fused
 //    multiply-add (exact product, one rounding of the small result) the accuracy does not
 //    depend on how large the logits themselves are.
-//  * Per element: 1 unpack, 1/2 max3, 1/2 min3, 1 fma, 1 exp2, 1 add, 1 fma.
+//  * Per element: 1 unpack, 1/2 max3, 1/2 min3, 1 fma, 1 exp2, 1 add, 1 fma: the vector ALUs
+//    are busy 98 % of the kernel's time, close behind memory -- which is why a sweep takes up to
+//    40 % longer while the chip's power management holds the shader clock down at the start of
+//    a sustained load.
 #include "aride_device.h"
 #include <hip/hip_ext.h>
 
 namespace aride {
 
-// Tuning parameters (the defaults are the measured best on MI355X for V = 32128 .. 151936).
-#ifndef ARIDE_SCORE_UNROLL
-#define ARIDE_SCORE_UNROLL 4    // 16-byte loads in flight per lane and batch
-#endif
-#ifndef ARIDE_SCORE_WAVES
-#define ARIDE_SCORE_WAVES 4     // waves (= rows) per workgroup
-#endif
-#ifndef ARIDE_SCORE_NT
-#define ARIDE_SCORE_NT 1        // 1: non-temporal loads
-#endif
-#ifndef ARIDE_SCORE_XCD_CHUNK
-#define ARIDE_SCORE_XCD_CHUNK 0 // consecutive workgroups' worth of rows per XCD and turn; 0: one eighth of all rows
-#endif
+constexpr int kScoreUnroll = 4;     // 16-byte loads in flight per lane and batch
+constexpr int kScoreWaves = 4;      // waves (= rows) per workgroup of the one-wave-per-row kernel
 
 // 16-byte vectors per row from which a row is shared by 4, 8, 16 waves (16 KB, 48 KB, 192 KB rows)
 constexpr int kSplit4MinVec = 1024, kSplit8MinVec = 3072, kSplit16MinVec = 12288;
@@ -116,11 +112,7 @@ __device__ __forceinline__ void unpack8(const u32x4& v, float* x) {
 }
 
 __device__ __forceinline__ u32x4 load16(const u32x4* p) {
-#if ARIDE_SCORE_NT
-    return __builtin_nontemporal_load(p);   // streamed once: keep it out of the caches' way
-#else
-    return *p;
-#endif
+    return __builtin_nontemporal_load(p);   // streamed once: keep it out of the caches' way (10 points of peak)
 }
 
 template <int NV>
@@ -140,23 +132,14 @@ __device__ __forceinline__ void to_common(float negk, float s, float t, float kc
 }
 
 template <int UNROLL>
-__global__ __launch_bounds__(64 * ARIDE_SCORE_WAVES) void k_score_rows(
+__global__ __launch_bounds__(64 * kScoreWaves) void k_score_rows(
     const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
     const int lane = threadIdx.x & 63;
-    // Workgroups are handed to the chip's 8 XCDs in turn (blockIdx mod 8).  The grid is a multiple
-    // of 8, and XCD x takes the x-th eighth of the rows (ARIDE_SCORE_XCD_CHUNK == 0) or, in
-    // every run of 8*CHUNK workgroups, the x-th run of CHUNK: each XCD, with its own L2 and its
-    // own paths to memory, then streams one contiguous region instead of every eighth 256 KB.
-    const long long per_xcd = gridDim.x >> 3, slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
-#if ARIDE_SCORE_XCD_CHUNK == 0
-    const long long vblock = xcd * per_xcd + slot;
-#else
-    const long long vblock = (slot / ARIDE_SCORE_XCD_CHUNK) * (8 * ARIDE_SCORE_XCD_CHUNK) +
-                             xcd * ARIDE_SCORE_XCD_CHUNK + slot % ARIDE_SCORE_XCD_CHUNK;
-#endif
-    const long long row = vblock * ARIDE_SCORE_WAVES + (threadIdx.x >> 6);
+    // the grid is a multiple of 8 and XCD x takes the x-th eighth of the rows: each XCD, with its own
+    // L2 and its own paths to memory, streams one contiguous region instead of every eighth 256 KB
+    const long long row = xcd_contiguous_block() * kScoreWaves + (threadIdx.x >> 6);
     if (row >= R) return;   // whole waves leave together; the kernel has no workgroup barrier
 
     const int tok = tokens[row];
@@ -350,7 +333,7 @@ hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long 
                                const int* tokens, int A, float* tok_logp, float* tok_ent,
                                float* step_logp, float* step_ent, uint32_t* status, hipStream_t st,
                                hipEvent_t sweep_start, hipEvent_t sweep_stop) {
-    constexpr int U = ARIDE_SCORE_UNROLL;
+    constexpr int U = kScoreUnroll;
     const int nvec = V >> 3;                                  // 16-byte vectors per row
     const bool fits_grid = R <= 0x7ffffff0ll;                 // one workgroup per row
     const dim3 rows8(round_up_8((unsigned)(fits_grid ? R : 0)));
@@ -364,13 +347,9 @@ hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long 
         launch_sweep(k_score_rows_split<U, 4>, rows8, dim3(256), st, sweep_start, sweep_stop, logits, R, V, stride,
                      tokens, tok_logp, tok_ent, status);
     else {
-        long long blocks = (R + ARIDE_SCORE_WAVES - 1) / ARIDE_SCORE_WAVES;
-#if ARIDE_SCORE_XCD_CHUNK == 0
+        long long blocks = (R + kScoreWaves - 1) / kScoreWaves;       // R <= 2^33 - 64 (checked by the caller)
         blocks = (blocks + 7) / 8 * 8;                       // the kernel's row mapping wants a multiple of 8
-#else
-        blocks = (blocks + 8 * ARIDE_SCORE_XCD_CHUNK - 1) / (8 * ARIDE_SCORE_XCD_CHUNK) * (8 * ARIDE_SCORE_XCD_CHUNK);
-#endif
-        launch_sweep(k_score_rows<U>, dim3((unsigned)blocks), dim3(64 * ARIDE_SCORE_WAVES), st, sweep_start,
+        launch_sweep(k_score_rows<U>, dim3((unsigned)blocks), dim3(64 * kScoreWaves), st, sweep_start,
                      sweep_stop, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
     }
     hipError_t err = hipGetLastError();

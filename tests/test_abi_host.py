@@ -61,6 +61,7 @@ def test_score_logits_rejects_bad_arguments(L):
     assert f(x, 4, 10, 9, t, 1, None, None, None, None, ws, 256, None) == b.E_SHAPE     # stride < V
     assert f(x, 4, 10, 10, t, 0, None, None, None, None, ws, 256, None) == b.E_SHAPE
     assert f(x, 4, 1 << 31, 1 << 31, t, 1, None, None, None, None, ws, 256, None) == b.E_RANGE
+    assert f(x, (1 << 33) - 60, 10, 10, t, 4, None, None, None, None, ws, 256, None) == b.E_RANGE     # ARIDE_MAX_ROWS + 4
     assert f(None, 4, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.E_NULL
     assert f(x, 4, 10, 10, None, 1, None, None, None, None, ws, 256, None) == b.E_NULL
     assert f(P(4098), 4, 10, 10, t, 1, None, None, None, None, ws, 256, None) == b.E_ALIGN
