@@ -312,10 +312,17 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
     float* aux = aux_all + wave * kChunk;
     const int span_end = (int)min((c_last + 1) * kChunk, (long long)N);     // the span's steps end here
 
+    // The span's last chunk, and the chunk after the span in case a trajectory runs on into it, are
+    // asked for before anything else: none of their addresses depends on the offsets.
+    const bool at_end = span_end >= N;
+    LaneIn cur = load_lane<MODE, PRIO, VEC>(g, (int)(c_last * kChunk), N);
+    LaneIn far;
+    if (!at_end) far = load_lane<MODE, PRIO, VEC>(g, span_end, N);
+    *reinterpret_cast<int4*>(tags + 4 * lane) = make_int4(0, 0, 0, 0);
+
     // ---- the trajectory that holds the span's last step.  The span that reaches N starts its walk
     // at the last trajectory (so that it meets the empty ones recorded at N); any other looks for
     // the smallest b with offsets[b+1] >= span_end.  offsets[B] = N >= span_end, so there is one.
-    const bool at_end = span_end >= N;
     int top = B - 1;
     if (!at_end) {
         int lo = 0, n = B;
@@ -344,18 +351,23 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
         }
         top = lo;
     }
-    // the span's last chunk, and the chunk after the span in case a trajectory runs on into it
-    LaneIn cur = load_lane<MODE, PRIO, VEC>(g, (int)(c_last * kChunk), N);
-    LaneIn far;
-    if (!at_end) far = load_lane<MODE, PRIO, VEC>(g, span_end, N);
-    *reinterpret_cast<int4*>(tags + 4 * lane) = make_int4(0, 0, 0, 0);
+    // What a lane reads of "its" trajectory in the first round of a walk down from `top`: trajectory
+    // top - lane (clamped to 0 when there is none, and then not used).  Lane 0's is `top` itself.
+    struct Walk { int o0, o1; float bt; };
+    auto walk_loads = [&](int from) {
+        const int bc = max(from - lane, 0);
+        Walk w;
+        w.o0 = g.offsets[bc]; w.o1 = g.offsets[bc + 1]; w.bt = g.boot ? g.boot[bc] : 0.f;
+        return w;
+    };
+    Walk wk = walk_loads(top);
     wave_lds_sync();
     float carry[2] = {0.f, 0.f};
     // ---- a trajectory that runs on past the span is scanned first, from its end down to the span
     if (!at_end) {
-        const int o0 = g.offsets[top], o1 = min(g.offsets[top + 1], N);
+        const int o0 = __shfl(wk.o0, 0, kWave), o1 = min(__shfl(wk.o1, 0, kWave), N);
         if (o0 < span_end && o1 > span_end) {
-            const float boot_end = g.boot ? g.boot[top] : 0.f;
+            const float boot_end = __shfl(wk.bt, 0, kWave);
             const int nfar = (int)(((long long)o1 - span_end + kChunk - 1) / kChunk);
             for (int m = nfar - 1; m >= 0; --m) {
                 const int c0 = (int)((long long)span_end + (long long)m * kChunk);   // span_end is a multiple of 256 here
@@ -367,14 +379,17 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
     for (long long c = c_last; c >= c_first; --c) {
         const int c0 = (int)(c * kChunk);
         const int c_end = (int)min((long long)c0 + kChunk, (long long)N);
-        if (c != c_last) cur = load_lane<MODE, PRIO, VEC>(g, c0, N);
+        if (c != c_last) { cur = load_lane<MODE, PRIO, VEC>(g, c0, N); wk = walk_loads(top); }
         // ---- mark the begins and ends of the trajectories that touch the chunk, walking down from
         // `top`: lane i takes trajectory top - i, top - i - 64, .. until one lies wholly below the
         // chunk.  A mark is (trajectory << 2) | 1 at a first step | 2 at a last step; beside it the
         // bootstrap value (at an end) or the length (at a begin that is not also the end).
         int below = -1;                               // the trajectory that holds step c0 - 1
+        bool first = true;
         for (int b = top - lane; b >= 0; b -= kWave) {
-            const int o0 = g.offsets[b], o1 = g.offsets[b + 1];
+            if (!first) wk = walk_loads(b + lane);    // (b + lane) - lane = b
+            first = false;
+            const int o0 = wk.o0, o1 = wk.o1;
             const bool empty = o1 <= o0;
             if (!empty && o0 < c0 && c0 <= o1) below = b;
             if (o1 < c0 || (o1 == c0 && !empty)) break;        // wholly below the chunk, and so are all before it
@@ -383,13 +398,12 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
                     if (g.pa.traj_prio && ((o0 >= c0 && o0 < c_end) || (o0 >= N && c_end >= N))) g.pa.traj_prio[b] = 0.f;
                 }
             } else {
-                const float bt = g.boot ? g.boot[b] : 0.f;
                 const int ps = o0 - c0, pe = o1 - 1 - c0;
                 if (ps == pe) {
-                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 3; aux[ps] = bt; }
+                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 3; aux[ps] = wk.bt; }
                 } else {
                     if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 1; aux[ps] = __int_as_float(o1 - o0); }
-                    if (pe >= 0 && pe < kChunk) { tags[pe] = (b << 2) | 2; aux[pe] = bt; }
+                    if (pe >= 0 && pe < kChunk) { tags[pe] = (b << 2) | 2; aux[pe] = wk.bt; }
                 }
             }
         }
