@@ -429,14 +429,17 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_step_priorities(cons
     store4<VEC>(g.pa.step_prio, t0, N, prio);
 }
 
-// Chunks per wave: about 3000 waves whatever the batch (measured on 0.66 M to 84 M steps: with
-// fewer the chip is not full, with many more the spans get short and a wave's search and its look
-// past its span's end stop being a small part of its work), a chunk per wave for small batches.
-constexpr long long kTargetWaves = 3072, kMaxSpan = 256;
+// Chunks per wave: a fixed number of waves whatever the batch, a chunk per wave for small batches.
+// With fewer waves the chip is not full, with many more the spans get short and a wave's search and
+// its look past its span's end stop being a small part of its work.  Measured on 0.66 M to 84 M
+// steps: about 3000 waves for the Retrace and V-trace scans (4 to 5 waves fit a SIMD at their
+// register count), about 6000 for the lighter Monte-Carlo and priority scans (6 to 8 fit).
+constexpr long long kTargetWavesRetrace = 3072, kTargetWavesLight = 6144, kMaxSpan = 256;
 
 template <int MODE, bool PRIO>
 static hipError_t flat_launch(const FlatArgs& g, hipStream_t st) {
     const long long nchunks = g.N > 0 ? ((long long)g.N + kChunk - 1) / kChunk : 1;
+    constexpr long long kTargetWaves = (MODE == kModeReturns || MODE == kModePriorities) ? kTargetWavesLight : kTargetWavesRetrace;
     long long span = (nchunks + kTargetWaves - 1) / kTargetWaves;
     if (span > kMaxSpan) span = kMaxSpan;
     const long long nwaves = (nchunks + span - 1) / span;
