@@ -25,15 +25,39 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per launch of the logit sweep from hardware counters (profiles/k_score_rows_learner_batch.md):
-# FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
-# plain 1 GiB copy kernel.  Valid only for the kernel source it was measured on (first 16 hex
-# digits of its sha256) and for the learner-batch workload; reported as null otherwise.
-TRAFFIC = {"source_sha256": "bedbb44b7456ad9e", "config": 1, "logit_rows": 82144,
-           "bytes_per_launch": 5287516475}
-# The same for the gradient sweep (profiles/k_actor_grad_learner_batch.md), scaled by the factors the copy gave.
-TRAFFIC_ACTOR = {"source_sha256": "968433073b711765", "config": 1, "logit_rows": 82144,
-                 "bytes_per_launch": 10559293543}
+# HBM bytes per step from hardware counters (profiles/*.md): FETCH_SIZE and WRITE_SIZE in KiB per
+# dispatch from two `rocprofv3 --pmc` runs of the very command, each scaled by what the same counter
+# reads for a plain 1 GiB copy kernel (x2.000 and x1.000), summed over the kernels the roofline entry
+# names.  An entry is valid only for the kernel source it was measured on (first 16 hex digits of
+# the file's sha256) and for its workload; anything else reports null.
+TRAFFIC = {
+    # the logit sweep (k_score_rows_split) on configs 0, 1, 2
+    ("scoring", 0): ("score_logits.hip", "8d90504f0b1d88a8", 164830208),
+    ("scoring", 1): ("score_logits.hip", "8d90504f0b1d88a8", 5287656550),
+    ("scoring", 2): ("score_logits.hip", "8d90504f0b1d88a8", 39844482458),
+    # k_actor_grad on config 1
+    ("actor_grad", 1): ("actor_grad.hip", "53dcf17a0ee283d4", 10559417139),
+    # k_flat_scan on config 3 at batch scales 1, 16, 64: (scale, one pass?)
+    ("retrace", (1, True)): ("retrace.hip", "f5309a53cdc93bad", 26555392),
+    ("retrace", (16, True)): ("retrace.hip", "f5309a53cdc93bad", 443062374),
+    ("retrace", (64, True)): ("retrace.hip", "f5309a53cdc93bad", 1717604557),
+    ("retrace", (64, False)): ("retrace.hip", "f5309a53cdc93bad", 2048710144),
+    # config 4: sample + tag + commit + the one sweep + its check + prefix; and the patched insert
+    ("replay", None): ("replay.hip", "ac06c3c53bf27522", 118010000),
+    ("insert", None): ("replay.hip", "ac06c3c53bf27522", 797000),
+}
+
+
+def _traffic(path, key):
+    import hashlib
+    entry = TRAFFIC.get((path, key))
+    if entry is None:
+        return None
+    fname, sha, nbytes = entry
+    src = os.path.join(ROOT, "paper_2410_14803_amd", "csrc", fname)
+    return nbytes if hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == sha else None
+
+
 METRIC = "trajectory-steps/sec scored (logits->Retrace->priority) + % peak HBM GB/s"
 
 
@@ -85,17 +109,10 @@ def bench_actor_grad(args, b, torch, cfg, logits, tokens, tok_logp, tok_ent, ste
         "config": {"workload": f"{cfg.name} (config {cfg.index}), actor_grad path", "traj_steps": N,
                    "logit_rows": R, "vocab": cfg.V, "grad_dtype": "bf16"},
         "roofline": {"bound": "hbm", "kernel": "k_actor_grad (+ k_actor_loss)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": _actor_traffic(args, R),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": _traffic("actor_grad", args.config) if R == 82144 else None,
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
         "cpu_baseline": cpu}), flush=True)
-
-
-def _actor_traffic(args, R):
-    import hashlib
-    src = os.path.join(ROOT, "paper_2410_14803_amd", "csrc", "actor_grad.hip")
-    same = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == TRAFFIC_ACTOR["source_sha256"]
-    ok = same and args.config == TRAFFIC_ACTOR["config"] and R == TRAFFIC_ACTOR["logit_rows"]
-    return TRAFFIC_ACTOR["bytes_per_launch"] if ok else None
 
 
 def _sweep_kernel_name(V):
@@ -183,7 +200,8 @@ def bench_retrace(args, b, torch, synth, dev):
         "roofline": {"bound": "hbm", "kernel": "k_flat_scan<Retrace, with priorities> (one launch)"
                      if args.one_pass else "k_flat_scan<Retrace> + k_flat_scan<priorities> (two launches)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": _traffic("retrace", (args.batch_scale, bool(args.one_pass))),
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms, "stream_mix_probe": mix},
         "cpu_baseline": cpu}), flush=True)
 
@@ -268,7 +286,7 @@ def bench_replay(args, b, torch, synth, dev):
         "config": {"workload": f"{cfg.name} (config {cfg.index})", "replay_entries": M, "draws": K, "alpha": cfg.alpha},
         "roofline": {"bound": "hbm", "kernel": "k_sample + k_update_tag/commit + k_super_sums + k_prefix_super",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": _traffic("replay", None),
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
         "cpu_baseline": cpu}), flush=True)
 
@@ -326,7 +344,8 @@ def bench_insert(args, b, torch, synth, dev):
                    "entries_per_insert": K, "alpha": cfg.alpha, "rebuild_every_insert": bool(args.rebuild_every_insert)},
         "roofline": {"bound": "hbm", "kernel": "k_insert_patch + k_patch_supers + k_patch_finish (+ two gated no-ops)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": None if args.rebuild_every_insert else _traffic("insert", None),
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
         "cpu_baseline": cpu}), flush=True)
 
@@ -346,6 +365,9 @@ def main():
                          "retrace: retrace_targets + compute_priorities on the long-scan workload (config 3). "
                          "replay: sample + update + index rebuild on the 2^24-entry buffer (config 4). "
                          "insert: circular insert of 65 536 entries into that buffer, index patched")
+    ap.add_argument("--launch-series", type=int, default=0,
+                    help="with --path scoring: report the duration of each of the first N pre-warm launches of the "
+                         "sweep and the shader clock read by a 10 us probe kernel after each of them")
     ap.add_argument("--two-calls", action="store_true",
                     help="with --path scoring or retrace: aride_retrace_targets and aride_compute_priorities as two "
                          "calls instead of the one call aride_retrace_priorities (one launch, TD errors and "
@@ -444,13 +466,23 @@ def main():
 
     # Pre-warm: the sweep alone, each launch timed like the timed steps below, so that the line can
     # show what the first window of a process costs beside the steady state (see --prewarm).
-    pre = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.prewarm)]
+    n_pre = max(args.prewarm, args.launch_series)
+    pre = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_pre)]
     for a, c in pre:
         a.record(); c.record()
+    clock_probe, clocks = None, None
+    if args.launch_series > 0:
+        import ctypes
+        lib_probe = ctypes.CDLL(os.path.join(ROOT, "paper_2410_14803_amd", "libaride_probe.so"))
+        lib_probe.aride_probe_clock.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+        clocks = torch.zeros(n_pre, 2, dtype=torch.int64, device=dev)
+        clock_probe = lambda i: lib_probe.aride_probe_clock(clocks[i].data_ptr(), 1000, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     for i, ev in enumerate(pre):
         b.score_logits(logits_ring[i % copies], tokens, cfg.A, ws, tok_logp=tok_logp, tok_ent=tok_ent,
                        step_logp=step_logp, step_ent=step_ent, sweep_events=ev)
+        if clock_probe is not None:
+            assert clock_probe(i) == 0
     torch.cuda.synchronize()
     pre_ms = [a.elapsed_time(c) for a, c in pre]
     for i in range(args.warmup):
@@ -492,11 +524,8 @@ def main():
     # dominant kernel: the logit sweep.  Algorithmic bytes per launch: every bf16 logit once,
     # one int32 token per row, two fp32 results per row.
     sweep_ms = sum(a.elapsed_time(c) for a, c in events.values()) / len(events)
-    import hashlib
-    src = os.path.join(ROOT, "paper_2410_14803_amd", "csrc", "score_logits.hip")
-    same_kernel = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] == TRAFFIC["source_sha256"]
-    traffic = TRAFFIC["bytes_per_launch"] if (same_kernel and args.config == TRAFFIC["config"]
-                                              and R == TRAFFIC["logit_rows"]) else None
+    expected_rows = {0: 2560, 1: 82144, 2: 131072}.get(args.config)
+    traffic = _traffic("scoring", args.config) if R == expected_rows else None
     alg_bytes = R * cfg.V * 2 + R * 4 + R * 8
     achieved = alg_bytes / (sweep_ms * 1e-3) / 1e9
     out = {
@@ -516,6 +545,10 @@ def main():
                      "ms_per_launch_slowest_of_first_window": max(pre_ms[:40]) if pre_ms else None},
     }
 
+    if clocks is not None:
+        ck = clocks.cpu().numpy()[:args.launch_series]
+        out["launch_series"] = {"sweep_us": [round(x * 1e3, 1) for x in pre_ms[:args.launch_series]],
+                                "shader_mhz_after_launch": [round(100.0 * c / max(w, 1)) for c, w in ck]}
     if not args.no_cpu_baseline:
         import oracle
         threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(os.cpu_count() or 1, 16)

@@ -63,3 +63,21 @@ extern "C" int aride_probe_mix(const void* in, void* out, int nin, int nout, siz
     else return -1;
     return hipGetLastError() == hipSuccess ? 0 : -7;
 }
+
+// The shader clock right now: cycles of the shader clock (clock64) per tick of the constant 100 MHz
+// counter (wall_clock64) over a spin of `wall_ticks` ticks.  out[0] = cycles, out[1] = ticks.
+// The spin ends after `wall_ticks` ticks or 2^22 polls, whichever comes first.
+__global__ void k_clock_probe(unsigned long long* __restrict__ out, unsigned long long wall_ticks) {
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    unsigned long long w1 = w0;
+    for (int polls = 0; polls < (1 << 22) && w1 - w0 < wall_ticks; ++polls) w1 = wall_clock64();
+    const unsigned long long c1 = clock64();
+    if (threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+}
+
+// out: device, two u64.  wall_ticks: length of the spin in 10 ns ticks (at most 100 000 = 1 ms).
+extern "C" int aride_probe_clock(void* out, unsigned long long wall_ticks, void* stream) {
+    if (!out || ((uintptr_t)out & 7) || wall_ticks == 0 || wall_ticks > 100000ull) return -1;
+    hipLaunchKernelGGL(k_clock_probe, dim3(1), dim3(64), 0, (hipStream_t)stream, (unsigned long long*)out, wall_ticks);
+    return hipGetLastError() == hipSuccess ? 0 : -7;
+}
