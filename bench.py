@@ -207,32 +207,45 @@ def bench_retrace(args, b, torch, synth, dev):
 
 
 def _mix_probe(torch, N, shape, dev):
-    """A bare kernel with the scan's access pattern (shape = arrays read, arrays written; 16 bytes per
-    lane and array, no scan): the rate the memory system allows that mix of streams on N steps."""
+    """Bare kernels with the scan's traffic and no scan (shape = arrays read, arrays written; 16 bytes
+    per lane and array): the rate the memory system allows that mix of streams on N steps, for a
+    workgroup per 4 KB in dispatch order and for the scan's own shape (a contiguous span per wave),
+    with plain and with non-temporal loads; and the read-only and write-only halves by themselves."""
     import ctypes
-    nin, nout = shape
     probe = ctypes.CDLL(os.path.join(ROOT, "paper_2410_14803_amd", "libaride_probe.so"))
     probe.aride_probe_mix.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
-                                      ctypes.c_void_p]
+                                      ctypes.c_int, ctypes.c_void_p]
     n = N // 4 * 4
-    ins = [torch.rand(n, device=dev) for _ in range(nin)]
-    outs = [torch.empty(n, device=dev) for _ in range(nout)]
-    pin = torch.tensor([t.data_ptr() for t in ins] + [0] * (6 - nin), dtype=torch.int64, device=dev)
-    pout = torch.tensor([t.data_ptr() for t in outs] + [0] * (4 - nout), dtype=torch.int64, device=dev)
+    ins = [torch.rand(n, device=dev) for _ in range(6)]
+    outs = [torch.empty(n, device=dev) for _ in range(4)]
+    pin = torch.tensor([t.data_ptr() for t in ins], dtype=torch.int64, device=dev)
+    pout = torch.tensor([t.data_ptr() for t in outs], dtype=torch.int64, device=dev)
     st = torch.cuda.current_stream().cuda_stream
-    go = lambda: probe.aride_probe_mix(pin.data_ptr(), pout.data_ptr(), nin, nout, n, st)
-    for _ in range(5):
-        assert go() == 0
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(20):
-        go()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / 20
-    gbps = n * 4 * (nin + nout) / (ms * 1e-3) / 1e9
-    return {"arrays_read": nin, "arrays_written": nout, "steps": n, "ms": ms, "GB/s": gbps, "frac": gbps / HBM_PEAK_GBPS}
+
+    def rate(nin, nout, pattern):
+        go = lambda: probe.aride_probe_mix(pin.data_ptr(), pout.data_ptr(), nin, nout, n, pattern, st)
+        for _ in range(5):
+            assert go() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            go()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        gbps = n * 4 * (nin + nout) / (ms * 1e-3) / 1e9
+        return {"ms": ms, "GB/s": gbps, "frac": gbps / HBM_PEAK_GBPS}
+
+    nin, nout = shape
+    out = {"arrays_read": nin, "arrays_written": nout, "steps": n}
+    out.update(rate(nin, nout, 0))
+    out["patterns"] = {
+        "block_per_4KB": rate(nin, nout, 0), "block_per_4KB_nt_loads": rate(nin, nout, 1),
+        "span_per_wave": rate(nin, nout, 2), "span_per_wave_nt_loads": rate(nin, nout, 3),
+        "read_only_6": rate(6, 0, 0), "read_only_6_nt_loads": rate(6, 0, 1), "write_only_4": rate(0, 4, 0),
+        "write_only_4_span_per_wave": rate(0, 4, 2)}
+    return out
 
 
 def bench_replay(args, b, torch, synth, dev):

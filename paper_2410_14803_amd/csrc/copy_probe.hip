@@ -28,38 +28,80 @@ extern "C" int aride_probe_copy(void* dst, const void* src, size_t nbytes, void*
 
 // The access pattern of the Retrace + priority scan with the scan taken out: NIN fp32 arrays
 // read and NOUT written, 16 bytes per lane and array, one pass, a trivial combination in between.
-// What this reaches is the ceiling the memory system sets for that mix of read and write streams
-// (a read-only sweep reaches 90 % of the HBM peak on this part, a mix of six read and four write
-// streams about 70 %).  Loads are plain, stores non-temporal, as in the scan.
-template <int NIN, int NOUT>
+// What this reaches is what the memory system allows that mix of read and write streams:
+//   SPANS = false  a workgroup per 4 KB of each array, in the order the workgroups are dispatched:
+//                  at any time the chip works on one compact window of every array;
+//   SPANS = true   the scan's own shape: about 3000 waves, each walking its own contiguous span
+//                  of every array from the end to the start, 1 KB per array at a time;
+//   NTL            non-temporal loads (stores are non-temporal throughout, as in the scan).
+template <int NIN, int NOUT, bool SPANS, bool NTL>
 __global__ __launch_bounds__(256) void k_mix_probe(const f32x4* const* __restrict__ in, f32x4* const* __restrict__ out,
-                                                   size_t nvec) {
+                                                   size_t nvec, size_t span) {
     // the grid is a multiple of 8; XCD x takes the x-th eighth
     const size_t blk = (size_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const size_t i = blk * 256 + threadIdx.x;
-    if (i >= nvec) return;
-    f32x4 v[NIN];
+    size_t first, last;                      // 16-byte units [first, last) in steps of 64 per wave
+    if (SPANS) {
+        const size_t wave = blk * 4 + (threadIdx.x >> 6);
+        first = wave * span * 64; last = first + span * 64;
+    } else {
+        first = blk * 256 + (threadIdx.x & ~(size_t)63); last = first + 64;
+    }
+    if (last > nvec) last = nvec;
+    for (size_t c = last; c > first;) {
+        c = c >= first + 64 ? c - 64 : first;
+        const size_t i = c + (threadIdx.x & 63);
+        if (i >= last) continue;
+        f32x4 acc = {1.f, 2.f, 3.f, 4.f};
+        if constexpr (NIN > 0) {
+            f32x4 v[NIN];
 #pragma unroll
-    for (int k = 0; k < NIN; ++k) v[k] = in[k][i];
-    f32x4 acc = v[0];
+            for (int k = 0; k < NIN; ++k) v[k] = NTL ? __builtin_nontemporal_load(in[k] + i) : in[k][i];
+            acc = v[0];
 #pragma unroll
-    for (int k = 1; k < NIN; ++k) acc = acc * 0.5f + v[k];
+            for (int k = 1; k < NIN; ++k) acc = acc * 0.5f + v[k];
+        }
+        if constexpr (NOUT == 0) {
+            if (acc.x == 1.2345678f) __builtin_nontemporal_store(acc, out[0] + i);    // keeps the loads alive
+        }
 #pragma unroll
-    for (int k = 0; k < NOUT; ++k) __builtin_nontemporal_store(acc + (float)k, out[k] + i);
+        for (int k = 0; k < NOUT; ++k) __builtin_nontemporal_store(acc + (float)k, out[k] + i);
+    }
+}
+
+template <int NIN, int NOUT>
+static void mix_launch(const f32x4* const* ins, f32x4* const* outs, size_t nvec, int pattern, hipStream_t st) {
+    const bool spans = pattern & 2, ntl = pattern & 1;
+    size_t span = 0, blocks;
+    if (spans) {
+        const size_t chunks = (nvec + 63) / 64;
+        span = (chunks + 3071) / 3072;
+        blocks = ((chunks + span - 1) / span + 3) / 4;
+    } else {
+        blocks = (nvec + 255) / 256;
+    }
+    const dim3 grid((unsigned)((blocks + 7) / 8 * 8)), block(256);
+    if (spans && ntl) hipLaunchKernelGGL((k_mix_probe<NIN, NOUT, true, true>), grid, block, 0, st, ins, outs, nvec, span);
+    else if (spans) hipLaunchKernelGGL((k_mix_probe<NIN, NOUT, true, false>), grid, block, 0, st, ins, outs, nvec, span);
+    else if (ntl) hipLaunchKernelGGL((k_mix_probe<NIN, NOUT, false, true>), grid, block, 0, st, ins, outs, nvec, span);
+    else hipLaunchKernelGGL((k_mix_probe<NIN, NOUT, false, false>), grid, block, 0, st, ins, outs, nvec, span);
 }
 
 // in / out: DEVICE arrays of 6 and 4 device pointers to fp32 arrays of n elements each (n a
-// multiple of 4, every array 16-byte aligned); nin in {3, 5, 6}, nout in {1, 3, 4}.
-extern "C" int aride_probe_mix(const void* in, void* out, int nin, int nout, size_t n, void* stream) {
-    if (!in || !out || (n & 3)) return -1;
+// multiple of 4, every array 16-byte aligned; out[0] must be valid even when nout is 0);
+// (nin, nout) in {(6,4), (5,3), (3,1), (6,0), (0,4)}; pattern: bit 0 = non-temporal loads,
+// bit 1 = a contiguous span per wave instead of a workgroup per 4 KB.
+extern "C" int aride_probe_mix(const void* in, void* out, int nin, int nout, size_t n, int pattern, void* stream) {
+    if (!in || !out || (n & 3) || pattern < 0 || pattern > 3 || n > ((size_t)1 << 36)) return -1;
     const size_t nvec = n / 4;
     if (nvec == 0) return 0;
-    const unsigned grid = (unsigned)(((nvec + 255) / 256 + 7) / 8 * 8);
     auto ins = (const f32x4* const*)in;
     auto outs = (f32x4* const*)out;
-    if (nin == 6 && nout == 4) hipLaunchKernelGGL((k_mix_probe<6, 4>), dim3(grid), dim3(256), 0, (hipStream_t)stream, ins, outs, nvec);
-    else if (nin == 5 && nout == 3) hipLaunchKernelGGL((k_mix_probe<5, 3>), dim3(grid), dim3(256), 0, (hipStream_t)stream, ins, outs, nvec);
-    else if (nin == 3 && nout == 1) hipLaunchKernelGGL((k_mix_probe<3, 1>), dim3(grid), dim3(256), 0, (hipStream_t)stream, ins, outs, nvec);
+    auto st = (hipStream_t)stream;
+    if (nin == 6 && nout == 4) mix_launch<6, 4>(ins, outs, nvec, pattern, st);
+    else if (nin == 5 && nout == 3) mix_launch<5, 3>(ins, outs, nvec, pattern, st);
+    else if (nin == 3 && nout == 1) mix_launch<3, 1>(ins, outs, nvec, pattern, st);
+    else if (nin == 6 && nout == 0) mix_launch<6, 0>(ins, outs, nvec, pattern, st);
+    else if (nin == 0 && nout == 4) mix_launch<0, 4>(ins, outs, nvec, pattern, st);
     else return -1;
     return hipGetLastError() == hipSuccess ? 0 : -7;
 }

@@ -89,10 +89,9 @@ __device__ __forceinline__ void store4(float* __restrict__ p, int t0, int limit,
     for (int j = 0; j < 4; ++j) if (t0 + j < limit) p[t0 + j] = x[j];
 }
 
-// What a lane reads for its four steps, and for the step after them when it is the wave's last lane.
+// What a lane reads for its four steps.
 struct LaneIn {
     float4 lp, lm, r, v, q, ent, td, rho;
-    float lp_n, lm_n, v_n;
 };
 
 // The chunk that starts at step c0; steps at or past `limit` do not exist.
@@ -115,16 +114,14 @@ __device__ __forceinline__ LaneIn load_lane(const FlatArgs& g, int c0, int limit
         in.rho = load4<VEC>(g.rho_in, t0, last);
     }
     if constexpr (PRIO) in.ent = load4<VEC>(g.pa.ent, t0, last);
-    if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
-        if (lane == kWave - 1 && t0 + 4 < limit) {      // the next chunk's first step
-            in.v_n = g.value[t0 + 4];
-            if constexpr (MODE == kModeRetrace) { in.lp_n = g.logp_pi[t0 + 4]; in.lm_n = g.logp_mu[t0 + 4]; }
-        }
-    }
     return in;
 }
 
 __device__ __forceinline__ float f4(const float4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+
+__device__ __forceinline__ float first_lane(float x) {
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
+}
 
 __device__ __forceinline__ int wave_max_i32(int v) {
 #pragma unroll
@@ -139,9 +136,12 @@ __device__ __forceinline__ int wave_max_i32(int v) {
 //         with bootstrap value `boot_end`; nothing is stored.
 // carry[c]: value of channel c entering the chunk from the right; on return, its value at the
 // chunk's first step (the same in every lane).
+// nxt: value estimate and importance ratio at the first step of the chunk above, which this wave
+// scanned just before (the step after this chunk's last); on return, those of this chunk's first step.
 template <int MODE, bool PRIO, bool VEC, bool MAIN>
 __device__ __forceinline__ void scan_chunk(const FlatArgs& g, const LaneIn& in, int c0, int limit,
-                                           float boot_end, int* tags, const float* aux, float (&carry)[2]) {
+                                           float boot_end, int* tags, const float* aux, float (&carry)[2],
+                                           float (&nxt)[2]) {
     constexpr int NC = (MODE == kModePriorities ? 0 : 1) + (PRIO ? 1 : 0);
     constexpr int CS = NC - 1;                      // the sum channel, when there is one
     static_assert(NC >= 1 && NC <= 2, "one or two channels");
@@ -174,12 +174,14 @@ __device__ __forceinline__ void scan_chunk(const FlatArgs& g, const LaneIn& in, 
     if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) rho[j] = valid[j] ? expf(f4(in.lp, j) - f4(in.lm, j)) : 0.f;
-        // the step after each of the four: the next element, the next lane's first, or what lane 63 loaded
+        // the step after each of the four: the next element, the next lane's first, or the chunk above's first
         float rho_n = __shfl_down(rho[0], 1, kWave), v_n = __shfl_down(in.v.x, 1, kWave);
         if (lane == kWave - 1) {
-            v_n = in.v_n;
-            if constexpr (MODE == kModeRetrace) rho_n = (t0 + 4 < limit) ? expf(in.lp_n - in.lm_n) : 0.f;
+            v_n = nxt[0];
+            rho_n = (t0 + 4 < limit) ? nxt[1] : 0.f;
         }
+        nxt[0] = first_lane(in.v.x);
+        nxt[1] = first_lane(rho[0]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             qv[j] = f4(in.q, j);                    // Q, or the value again when there is no Q
@@ -363,6 +365,12 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
     Walk wk = walk_loads(top);
     wave_lds_sync();
     float carry[2] = {0.f, 0.f};
+    // the step after the span's last: the first of the chunk asked for above (a far chunk scanned
+    // below leaves the same two values)
+    float nxt[2] = {0.f, 0.f};
+    if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
+        if (!at_end) { nxt[0] = first_lane(far.v.x); nxt[1] = expf(first_lane(far.lp.x) - first_lane(far.lm.x)); }
+    }
     // ---- a trajectory that runs on past the span is scanned first, from its end down to the span
     if (!at_end) {
         const int o0 = __shfl(wk.o0, 0, kWave), o1 = min(__shfl(wk.o1, 0, kWave), N);
@@ -372,7 +380,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
             for (int m = nfar - 1; m >= 0; --m) {
                 const int c0 = (int)((long long)span_end + (long long)m * kChunk);   // span_end is a multiple of 256 here
                 if (nfar > 1) far = load_lane<MODE, PRIO, VEC>(g, c0, o1);           // else: loaded above already
-                scan_chunk<MODE, PRIO, VEC, false>(g, far, c0, o1, boot_end, tags, aux, carry);
+                scan_chunk<MODE, PRIO, VEC, false>(g, far, c0, o1, boot_end, tags, aux, carry, nxt);
             }
         }
     }
@@ -409,7 +417,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
         }
         below = wave_max_i32(below);
         wave_lds_sync();
-        scan_chunk<MODE, PRIO, VEC, true>(g, cur, c0, N, 0.f, tags, aux, carry);
+        scan_chunk<MODE, PRIO, VEC, true>(g, cur, c0, N, 0.f, tags, aux, carry, nxt);
         top = below;
     }
 }
