@@ -10,7 +10,9 @@
 //     In a chunk lane l holds four consecutive steps: with 16-byte aligned arrays every load and
 //     store is one contiguous 16-byte access per lane, every lane is busy whatever the mix of
 //     lengths, no address depends on the offsets array, and all loads of a chunk go out back to
-//     back.  The scan's values at a chunk's first step stay in registers for the chunk below.
+//     back.  The scan's values at a chunk's first step stay in registers for the chunk below, and
+//     so do the value estimate and ratio of that step, which the chunk below needs as "the step
+//     after".  While a chunk is scanned the loads of the chunk below are already in flight.
 //   * where trajectories begin and end inside a chunk is marked in the wave's own 2 KB of LDS:
 //     lane i looks at trajectory top - i, walking down from the trajectory `top` that holds the
 //     chunk's last step; the trajectory that holds the step before the chunk is the next `top`.
@@ -94,12 +96,13 @@ struct LaneIn {
     float4 lp, lm, r, v, q, ent, td, rho;
 };
 
-// The chunk that starts at step c0; steps at or past `limit` do not exist.
+// The chunk that starts at step c0; steps at or past `limit` (at least 1) do not exist.  Only the
+// members the mode reads are set.  Nothing here branches or writes a register that is not a load's
+// destination: a wave can then have several chunks' loads in flight and wait for each by itself.
 template <int MODE, bool PRIO, bool VEC>
 __device__ __forceinline__ LaneIn load_lane(const FlatArgs& g, int c0, int limit) {
     const int lane = threadIdx.x & 63, t0 = c0 + 4 * lane;
-    LaneIn in = {};
-    if (__builtin_amdgcn_readfirstlane(limit) <= 0) return in;      // no steps at all (and maybe no arrays)
+    LaneIn in;
     const int last = limit - 1;
     if constexpr (MODE == kModeRetrace || MODE == kModeVtrace) {
         in.lp = load4<VEC>(g.logp_pi, t0, last);
@@ -297,7 +300,10 @@ __device__ __forceinline__ void scan_chunk(const FlatArgs& g, const LaneIn& in, 
     }
 }
 
-// Each wave owns `span` consecutive chunks and walks them from the last to the first.
+// Each wave owns `span` consecutive chunks and walks them from the last to the first.  The loads of
+// the chunk below are in flight while a chunk is scanned (two sets of registers that swap roles),
+// and its marks are set while the scanned chunk's stores drain: what the wave waits for are loads
+// it asked for a whole chunk earlier.
 template <int MODE, bool PRIO, bool VEC>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const FlatArgs g, const int span) {
     __shared__ __attribute__((aligned(16))) int tags_all[kWavesPerBlock * kChunk];
@@ -305,19 +311,27 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int N = g.N, B = g.B;
     // the grid is the number of spans rounded up to whole workgroups and to a multiple of 8
-    // workgroups; XCD x takes the x-th eighth
-    const long long nchunks = N > 0 ? ((long long)N + kChunk - 1) / kChunk : 1;
-    const long long c_first = (xcd_contiguous_block() * kWavesPerBlock + wave) * span;
-    if (c_first >= nchunks) return;                   // whole waves leave; there is no workgroup barrier below
-    const long long c_last = min(c_first + span, nchunks) - 1;
+    // workgroups; XCD x takes the x-th eighth.  What is the same in every lane of the wave is
+    // kept where the compiler can see that it is.
+    const int nchunks = N > 0 ? (int)(((long long)N + kChunk - 1) / kChunk) : 1;
+    const long long first_ll = (xcd_contiguous_block() * kWavesPerBlock + wave) * span;
+    if (first_ll >= nchunks) return;                  // whole waves leave; there is no workgroup barrier below
+    if (N <= 0) {                                     // no steps (and maybe no arrays): every trajectory is empty
+        if constexpr (PRIO) {
+            if (g.pa.traj_prio) for (int b = lane; b < B; b += kWave) g.pa.traj_prio[b] = 0.f;
+        }
+        return;
+    }
+    const int c_first = __builtin_amdgcn_readfirstlane((int)first_ll);
+    const int c_last = min(c_first + span, nchunks) - 1;
     int* tags = tags_all + wave * kChunk;
     float* aux = aux_all + wave * kChunk;
-    const int span_end = (int)min((c_last + 1) * kChunk, (long long)N);     // the span's steps end here
+    const int span_end = (int)min((long long)(c_last + 1) * kChunk, (long long)N);     // the span's steps end here
 
     // The span's last chunk, and the chunk after the span in case a trajectory runs on into it, are
     // asked for before anything else: none of their addresses depends on the offsets.
     const bool at_end = span_end >= N;
-    LaneIn cur = load_lane<MODE, PRIO, VEC>(g, (int)(c_last * kChunk), N);
+    LaneIn even = load_lane<MODE, PRIO, VEC>(g, c_last * kChunk, N), odd;
     LaneIn far;
     if (!at_end) far = load_lane<MODE, PRIO, VEC>(g, span_end, N);
     *reinterpret_cast<int4*>(tags + 4 * lane) = make_int4(0, 0, 0, 0);
@@ -351,7 +365,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
             n = max(nhi - nlo, 1);
             lo = nlo;
         }
-        top = lo;
+        top = __builtin_amdgcn_readfirstlane(lo);
     }
     // What a lane reads of "its" trajectory in the first round of a walk down from `top`: trajectory
     // top - lane (clamped to 0 when there is none, and then not used).  Lane 0's is `top` itself.
@@ -361,6 +375,42 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
         Walk w;
         w.o0 = g.offsets[bc]; w.o1 = g.offsets[bc + 1]; w.bt = g.boot ? g.boot[bc] : 0.f;
         return w;
+    };
+    // Marks the begins and ends of the trajectories that touch chunk c, walking down from the
+    // trajectory `from` that holds the chunk's last step: lane i takes trajectory from - i,
+    // from - i - 64, .. until one lies wholly below the chunk (wk: what walk_loads(from) read).
+    // A mark is (trajectory << 2) | 1 at a first step | 2 at a last step; beside it the bootstrap
+    // value (at an end) or the length (at a begin that is not also the end).  Returns the
+    // trajectory that holds the step before the chunk (-1: none).
+    auto mark_chunk = [&](int c, int from, Walk wk) {
+        const int c0 = c * kChunk;
+        const int c_end = (int)min((long long)c0 + kChunk, (long long)N);
+        int below = -1;
+        bool first = true;
+        for (int b = from - lane; b >= 0; b -= kWave) {
+            if (!first) wk = walk_loads(b + lane);    // (b + lane) - lane = b
+            first = false;
+            const int o0 = wk.o0, o1 = wk.o1;
+            const bool empty = o1 <= o0;
+            if (!empty && o0 < c0 && c0 <= o1) below = b;
+            if (o1 < c0 || (o1 == c0 && !empty)) break;        // wholly below the chunk, and so are all before it
+            if (empty) {                              // mean priority 0, written by the chunk that owns position o0
+                if constexpr (PRIO) {
+                    if (g.pa.traj_prio && ((o0 >= c0 && o0 < c_end) || (o0 >= N && c_end >= N))) g.pa.traj_prio[b] = 0.f;
+                }
+            } else {
+                const int ps = o0 - c0, pe = o1 - 1 - c0;
+                if (ps == pe) {
+                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 3; aux[ps] = wk.bt; }
+                } else {
+                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 1; aux[ps] = __int_as_float(o1 - o0); }
+                    if (pe >= 0 && pe < kChunk) { tags[pe] = (b << 2) | 2; aux[pe] = wk.bt; }
+                }
+            }
+        }
+        below = __builtin_amdgcn_readfirstlane(wave_max_i32(below));
+        wave_lds_sync();
+        return below;
     };
     Walk wk = walk_loads(top);
     wave_lds_sync();
@@ -384,41 +434,27 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
             }
         }
     }
-    for (long long c = c_last; c >= c_first; --c) {
-        const int c0 = (int)(c * kChunk);
-        const int c_end = (int)min((long long)c0 + kChunk, (long long)N);
-        if (c != c_last) { cur = load_lane<MODE, PRIO, VEC>(g, c0, N); wk = walk_loads(top); }
-        // ---- mark the begins and ends of the trajectories that touch the chunk, walking down from
-        // `top`: lane i takes trajectory top - i, top - i - 64, .. until one lies wholly below the
-        // chunk.  A mark is (trajectory << 2) | 1 at a first step | 2 at a last step; beside it the
-        // bootstrap value (at an end) or the length (at a begin that is not also the end).
-        int below = -1;                               // the trajectory that holds step c0 - 1
-        bool first = true;
-        for (int b = top - lane; b >= 0; b -= kWave) {
-            if (!first) wk = walk_loads(b + lane);    // (b + lane) - lane = b
-            first = false;
-            const int o0 = wk.o0, o1 = wk.o1;
-            const bool empty = o1 <= o0;
-            if (!empty && o0 < c0 && c0 <= o1) below = b;
-            if (o1 < c0 || (o1 == c0 && !empty)) break;        // wholly below the chunk, and so are all before it
-            if (empty) {                              // mean priority 0, written by the chunk that owns position o0
-                if constexpr (PRIO) {
-                    if (g.pa.traj_prio && ((o0 >= c0 && o0 < c_end) || (o0 >= N && c_end >= N))) g.pa.traj_prio[b] = 0.f;
-                }
-            } else {
-                const int ps = o0 - c0, pe = o1 - 1 - c0;
-                if (ps == pe) {
-                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 3; aux[ps] = wk.bt; }
-                } else {
-                    if (ps >= 0 && ps < kChunk) { tags[ps] = (b << 2) | 1; aux[ps] = __int_as_float(o1 - o0); }
-                    if (pe >= 0 && pe < kChunk) { tags[pe] = (b << 2) | 2; aux[pe] = wk.bt; }
-                }
-            }
-        }
-        below = wave_max_i32(below);
-        wave_lds_sync();
-        scan_chunk<MODE, PRIO, VEC, true>(g, cur, c0, N, 0.f, tags, aux, carry, nxt);
-        top = below;
+    // ---- the span.  Before a chunk is scanned its marks are set and `top` is the trajectory that
+    // holds the step before it.  One turn: ask for the next chunk's offsets and data (the span's
+    // first chunk once more when there is no next: loads that are not used, and no branch), scan
+    // this chunk, then set the next chunk's marks.
+    int c = c_last;
+    top = mark_chunk(c, top, wk);
+    // false once the span's first chunk has been scanned
+    auto turn = [&](const LaneIn& cur, LaneIn& next) {
+        wk = walk_loads(top);
+        next = load_lane<MODE, PRIO, VEC>(g, max(c - 1, c_first) * kChunk, N);
+        scan_chunk<MODE, PRIO, VEC, true>(g, cur, c * kChunk, N, 0.f, tags, aux, carry, nxt);
+        if (--c < c_first) return false;
+        top = mark_chunk(c, top, wk);
+        return true;
+    };
+    // (the first turn stands outside the loop so that the loop is entered, like it is repeated,
+    // with a turn's loads and stores in flight and nothing else)
+    if (!turn(even, odd)) return;
+    for (;;) {
+        if (!turn(odd, even)) return;
+        if (!turn(even, odd)) return;
     }
 }
 
