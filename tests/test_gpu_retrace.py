@@ -350,7 +350,9 @@ def test_flat_scan_tile_edges_and_long_trajectories(oracle, lens):
     one_pass_against_oracle(oracle, off_np, 4321 + len(lens), 0.97, 0.9, "tile edges v-trace", vtrace=True, use_boot=False)
 
 
-@pytest.mark.parametrize("n_steps", [700_000, 1_200_000, 2_500_000])      # spans of 1, 2 and 4 chunks per wave
+# spans of 1, 2, 3, 4 and 5 chunks per wave for the Retrace scans (1, 1, 2, 2 and 3 for the lighter
+# modes): the loop that keeps the next chunk's loads in flight ends after an odd and an even turn
+@pytest.mark.parametrize("n_steps", [700_000, 1_200_000, 2_000_000, 2_500_000, 3_500_000])
 def test_flat_scan_several_chunks_per_wave(oracle, n_steps):
     rng = np.random.default_rng(n_steps)
     lens = []
