@@ -38,10 +38,10 @@ TRAFFIC = {
     # k_actor_grad on config 1
     ("actor_grad", 1): ("actor_grad.hip", "53dcf17a0ee283d4", 10559417139),
     # k_flat_scan on config 3 at batch scales 1, 16, 64: (scale, one pass?)
-    ("retrace", (1, True)): ("retrace.hip", "10a80bcbd39fb196", 26557645),
-    ("retrace", (16, True)): ("retrace.hip", "10a80bcbd39fb196", 439366554),
-    ("retrace", (64, True)): ("retrace.hip", "10a80bcbd39fb196", 1708193485),
-    ("retrace", (64, False)): ("retrace.hip", "10a80bcbd39fb196", 2059063808),
+    ("retrace", (1, True)): ("retrace.hip", "c321b09416a5e31a", 26570957),
+    ("retrace", (16, True)): ("retrace.hip", "c321b09416a5e31a", 439354368),
+    ("retrace", (64, True)): ("retrace.hip", "c321b09416a5e31a", 1708336128),
+    ("retrace", (64, False)): ("retrace.hip", "c321b09416a5e31a", 2059197645),
     # config 4: sample + tag + commit + the one sweep + its check + prefix; and the patched insert
     ("replay", None): ("replay.hip", "ac06c3c53bf27522", 118010000),
     ("insert", None): ("replay.hip", "ac06c3c53bf27522", 797000),

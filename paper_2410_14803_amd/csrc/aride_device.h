@@ -152,7 +152,7 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
     return v;
 }
 
-// What compute_priorities needs when it rides along with the Retrace scan (k_retrace, PRIO).
+// What compute_priorities needs when it rides along with the Retrace scan (k_flat_scan, PRIO).
 struct PrioArgs {
     const float* ent;
     float w_td, w_rho, w_ent, inv_td_scale, inv_ent_scale, eps;

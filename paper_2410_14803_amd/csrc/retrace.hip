@@ -17,7 +17,8 @@
 //     lane i looks at trajectory top - i, walking down from the trajectory `top` that holds the
 //     chunk's last step; the trajectory that holds the step before the chunk is the next `top`.
 //     Only a span's first `top` is searched for: one probe around the place an even spread of
-//     lengths would put it, else a 64-ary search through the offsets.
+//     lengths would put it (what it reads also serves the first walk), else a 64-ary search
+//     through the offsets.
 //   * the value entering a span from the right is whatever the trajectory crossing its right end
 //     contributes: the wave scans that trajectory's remainder first (for trajectories of up to 256
 //     steps that is one chunk, whose loads go out with the span's first).  No wave ever waits for
@@ -339,7 +340,18 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
     // ---- the trajectory that holds the span's last step.  The span that reaches N starts its walk
     // at the last trajectory (so that it meets the empty ones recorded at N); any other looks for
     // the smallest b with offsets[b+1] >= span_end.  offsets[B] = N >= span_end, so there is one.
+    // What a lane reads of "its" trajectory in the first round of a walk down from `top`: trajectory
+    // top - lane (clamped to 0 when there is none, and then not used).  Lane 0's is `top` itself.
+    struct Walk { int o0, o1; float bt; };
+    auto walk_loads = [&](int from) {
+        const int bc = max(from - lane, 0);
+        Walk w;
+        w.o0 = g.offsets[bc]; w.o1 = g.offsets[bc + 1]; w.bt = g.boot ? g.boot[bc] : 0.f;
+        return w;
+    };
     int top = B - 1;
+    Walk wk;
+    bool have_wk = false;
     if (!at_end) {
         int lo = 0, n = B;
         // First a guess: were all trajectories equally long, step span_end would lie in trajectory
@@ -349,10 +361,26 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
             const int guess = (int)((long long)span_end * B / N);
             const int w0 = max(min(guess - 32, B - kWave), 0);          // window [w0, w0 + 64) inside [0, B)
             const int p = min(w0 + lane, B - 1);
-            const unsigned long long m = __ballot(g.offsets[p + 1] >= span_end);
+            const int po0 = g.offsets[p], po1 = g.offsets[p + 1];
+            const float pbt = g.boot ? g.boot[p] : 0.f;
+            const unsigned long long m = __ballot(po1 >= span_end);
             // the answer is inside the window when its first trajectory fails the test (or is
             // trajectory 0) and some later one passes
-            if (m != 0ull && (!(m & 1ull) || w0 == 0)) { lo = w0 + __ffsll((long long)m) - 1; n = 1; }
+            if (m != 0ull && (!(m & 1ull) || w0 == 0)) {
+                lo = w0 + __ffsll((long long)m) - 1; n = 1;
+                // The probe has then read what the walk over the span's last chunk wants of the
+                // trajectories lo, lo - 1, .. down to w0 (a second round trip saved), and whatever
+                // lies below the window lies wholly below that chunk if the window's lowest
+                // trajectory ends before the chunk starts: offsets[w0 + 1] < the chunk's first step.
+                const int o1_w0 = __builtin_amdgcn_readfirstlane(po1);
+                if (w0 == 0 || o1_w0 < c_last * kChunk) {
+                    const int j = lo - lane - w0;                   // the lane that read trajectory lo - lane
+                    const int src = max(j, 0);
+                    wk.o0 = __shfl(po0, src, kWave); wk.o1 = __shfl(po1, src, kWave); wk.bt = __shfl(pbt, src, kWave);
+                    if (j < 0) { wk.o0 = -1; wk.o1 = -1; }          // reads as: empty, and below every chunk
+                    have_wk = true;
+                }
+            }
         }
         // Else a 64-ary search: each round keeps the sixty-fourth of the candidates [lo, lo+n) that holds it.
         while (n > 1) {
@@ -367,15 +395,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
         }
         top = __builtin_amdgcn_readfirstlane(lo);
     }
-    // What a lane reads of "its" trajectory in the first round of a walk down from `top`: trajectory
-    // top - lane (clamped to 0 when there is none, and then not used).  Lane 0's is `top` itself.
-    struct Walk { int o0, o1; float bt; };
-    auto walk_loads = [&](int from) {
-        const int bc = max(from - lane, 0);
-        Walk w;
-        w.o0 = g.offsets[bc]; w.o1 = g.offsets[bc + 1]; w.bt = g.boot ? g.boot[bc] : 0.f;
-        return w;
-    };
     // Marks the begins and ends of the trajectories that touch chunk c, walking down from the
     // trajectory `from` that holds the chunk's last step: lane i takes trajectory from - i,
     // from - i - 64, .. until one lies wholly below the chunk (wk: what walk_loads(from) read).
@@ -412,7 +431,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
         wave_lds_sync();
         return below;
     };
-    Walk wk = walk_loads(top);
+    if (!have_wk) wk = walk_loads(top);
     wave_lds_sync();
     float carry[2] = {0.f, 0.f};
     // the step after the span's last: the first of the chunk asked for above (a far chunk scanned
@@ -437,7 +456,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void k_flat_scan(const Flat
     // ---- the span.  Before a chunk is scanned its marks are set and `top` is the trajectory that
     // holds the step before it.  One turn: ask for the next chunk's offsets and data (the span's
     // first chunk once more when there is no next: loads that are not used, and no branch), scan
-    // this chunk, then set the next chunk's marks.
+    // this chunk, then set the next chunk's marks.  (A last turn of its own, with nothing asked
+    // for, costs 40 more registers and gains nothing.)
     int c = c_last;
     top = mark_chunk(c, top, wk);
     // false once the span's first chunk has been scanned

@@ -363,6 +363,18 @@ def test_flat_scan_several_chunks_per_wave(oracle, n_steps):
     one_pass_against_oracle(oracle, off_np, 99, 0.99, 0.95, f"N={n_steps}")
 
 
+@pytest.mark.parametrize("hi", [4, 9])
+def test_flat_scan_many_tiny_trajectories(oracle, hi):
+    # dozens to hundreds of trajectories per chunk (empty ones among them): the walk over the offsets
+    # takes several rounds, and the 64 trajectories a span's first probe reads do not reach below
+    # the span's last chunk
+    rng = np.random.default_rng(hi)
+    lens = list(rng.integers(0, hi, 300_000)) + [700] + list(rng.integers(0, hi, 1000)) + [0, 0, 0]
+    print(f"case {len(lens)} trajectories, {sum(lens)} steps", flush=True)
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    one_pass_against_oracle(oracle, off_np, 77 + hi, 0.95, 0.9, f"tiny trajectories < {hi}")
+
+
 def test_flat_scan_keeps_trajectories_apart(oracle):
     # an infinity, a NaN or a huge value in one trajectory stays there: the step before a
     # trajectory's end takes nothing from the next trajectory, not even 0 * inf
