@@ -41,10 +41,13 @@ TRAFFIC = {
     ("retrace", (1, True)): ("retrace.hip", "c321b09416a5e31a", 26570957),
     ("retrace", (16, True)): ("retrace.hip", "c321b09416a5e31a", 439354368),
     ("retrace", (64, True)): ("retrace.hip", "c321b09416a5e31a", 1708336128),
+    ("retrace", (1, False)): ("retrace.hip", "c321b09416a5e31a", 31978496),
+    ("retrace", (16, False)): ("retrace.hip", "c321b09416a5e31a", 537822106),
     ("retrace", (64, False)): ("retrace.hip", "c321b09416a5e31a", 2059197645),
     # config 4: sample + tag + commit + the one sweep + its check + prefix; and the patched insert
     ("replay", None): ("replay.hip", "ac06c3c53bf27522", 118010000),
     ("insert", None): ("replay.hip", "ac06c3c53bf27522", 797000),
+    ("insert", "rebuild"): ("replay.hip", "ac06c3c53bf27522", 79412000),    # the patched insert + a full rebuild
 }
 
 
@@ -358,7 +361,7 @@ def bench_insert(args, b, torch, synth, dev):
         "roofline": {"bound": "hbm", "kernel": "k_insert_patch + k_patch_supers + k_patch_finish (+ two gated no-ops)",
                      "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": None if args.rebuild_every_insert else _traffic("insert", None),
+                     "traffic": _traffic("insert", "rebuild" if args.rebuild_every_insert else None),
                      "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": ms},
         "cpu_baseline": cpu}), flush=True)
 
