@@ -363,6 +363,16 @@ def test_flat_scan_several_chunks_per_wave(oracle, n_steps):
     one_pass_against_oracle(oracle, off_np, 99, 0.99, 0.95, f"N={n_steps}")
 
 
+@pytest.mark.parametrize("scale", [16, 64])
+def test_long_scan_batch_at_the_sizes_the_rates_are_quoted_on(oracle, scale):
+    # the long-scan workload with 16 and 64 times as many trajectories (10.5 M and 42 M steps):
+    # spans of 14 and 54 chunks per wave, the launches the bench times
+    cfg = synth.scaled(synth.CONFIGS[3], B=synth.CONFIGS[3].B * scale)
+    off_np = synth.trajectory_offsets(cfg, synth.BASE_SEED + cfg.index)
+    print(f"case {len(off_np) - 1} trajectories, {int(off_np[-1])} steps", flush=True)
+    one_pass_against_oracle(oracle, off_np, 31 + scale, cfg.gamma, cfg.lam, f"long scan x{scale}")
+
+
 @pytest.mark.parametrize("hi", [4, 9])
 def test_flat_scan_many_tiny_trajectories(oracle, hi):
     # dozens to hundreds of trajectories per chunk (empty ones among them): the walk over the offsets
