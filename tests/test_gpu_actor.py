@@ -16,7 +16,7 @@ import torch
 
 from paper_2410_14803_amd import binding as b
 from paper_2410_14803_amd import synth
-from _util import assert_close, bits_of, grad_bound, npf
+from _util import assert_close, bits_of, grad_bound, host_threads, npf
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -132,7 +132,7 @@ def test_config1_full_size_sampled(oracle):
                       target, base, beta, scale, penalty=pen, lambda_pen=0.1, grad=g16, loss=loss)
     torch.cuda.synchronize()
     g = np.random.default_rng(3)
-    rows = np.unique(np.concatenate([[0, R - 1], g.integers(0, R, 200)]))
+    rows = np.unique(np.concatenate([[0, R - 1], g.integers(0, R, 2000)]))
     rt = torch.as_tensor(rows, device=DEV)
     steps = rows // cfg.A
     _, o_grad = oracle.actor_loss_grad(bits_of(logits[rt]), npf(tokens)[rows], 1, npf(rho)[steps], npf(target)[steps],
@@ -151,3 +151,53 @@ def test_config1_full_size_sampled(oracle):
     # softmax is shift invariant: every gradient row sums to ~0 (bf16 rounding noise only)
     sums = g16[rt].float().sum(1).abs().cpu().numpy()
     assert np.all(sums <= 64 * 2.0 ** -8 * scale * (coef + beta * 12) + 1e-12)
+
+
+def test_config1_full_size_every_row(oracle):
+    # every element of the bf16 gradient of the learner batch (82 144 rows x 32 128) against the
+    # oracle: rows go to the host once, the oracle and the comparison run over blocks of rows on
+    # all host threads (the oracle's routine is called per block with A = 1 and per-row factors)
+    from concurrent.futures import ThreadPoolExecutor
+    cfg = synth.CONFIGS[1]
+    seed = synth.BASE_SEED + cfg.index
+    off = synth.trajectory_offsets(cfg, seed)
+    N = int(off[-1]); R = N * cfg.A; V = cfg.V
+    print(f"config1 actor, every row: R={R}", flush=True)
+    logits = synth.logits_bf16(R, V, seed + 1, DEV)
+    tokens = synth.action_tokens(logits, seed + 2)
+    fp = first_pass(logits, tokens, cfg.A)
+    rho, target, base, _ = step_inputs(N, 78)
+    beta, scale = 0.01, 1.0 / N
+    g16 = torch.empty((R, V), dtype=torch.bfloat16, device=DEV)
+    b.actor_loss_grad(logits, tokens, cfg.A, fp["tok_logp"], fp["tok_ent"], fp["step_logp"], fp["step_ent"], rho,
+                      target, base, beta, scale, grad=g16)
+    torch.cuda.synchronize()
+    bits = bits_of(logits)
+    gbits = bits_of(g16)
+    del logits, g16
+    tok = npf(tokens)
+    rows_of = lambda t: np.repeat(npf(t).astype(np.float64), cfg.A)
+    rho_r, target_r, base_r = rows_of(rho), rows_of(target), rows_of(base)
+    g_logp, g_ent = npf(fp["tok_logp"]), npf(fp["tok_ent"])
+    o_score = oracle.score_logits(bits, tok, 1, nthreads=host_threads())
+    print("first sweep compared, gradient blocks next", flush=True)
+    assert_close(g_logp, o_score["tok_logp"], float(np.log(V)), "tok_logp")
+
+    def block(r0):
+        r1 = min(R, r0 + 512)
+        sl = slice(r0, r1)
+        _, want = oracle.actor_loss_grad(bits[sl], tok[sl], 1, rho_r[sl], target_r[sl], base_r[sl], beta, scale)
+        got = (gbits[sl].astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+        extra = grad_bound(bits[sl], tok[sl], V, rho_r[sl] * (target_r[sl] - base_r[sl]), beta, scale,
+                           o_score["tok_logp"][sl], o_score["tok_ent"][sl], g_logp[sl], g_ent[sl])
+        bound = 2.0 ** -7 * np.abs(want) + extra
+        err = np.abs(got - want)
+        bad = int(np.count_nonzero(~(err <= bound)))
+        return bad, float(np.max(err / bound))
+
+    with ThreadPoolExecutor(max_workers=host_threads()) as pool:
+        results = list(pool.map(block, range(0, R, 512)))
+    bad = sum(r[0] for r in results)
+    worst = max(r[1] for r in results)
+    print(f"worst ratio to the bound {worst:.3f}", flush=True)
+    assert bad == 0, f"{bad} gradient elements beyond one bf16 ulp plus the inherited bound; worst ratio {worst:.3f}"
