@@ -45,9 +45,9 @@ TRAFFIC = {
     ("retrace", (16, False)): ("retrace.hip", "c321b09416a5e31a", 537822106),
     ("retrace", (64, False)): ("retrace.hip", "c321b09416a5e31a", 2059197645),
     # config 4: sample + tag + commit + the one sweep + its check + prefix; and the patched insert
-    ("replay", None): ("replay.hip", "ac06c3c53bf27522", 118010000),
-    ("insert", None): ("replay.hip", "ac06c3c53bf27522", 797000),
-    ("insert", "rebuild"): ("replay.hip", "ac06c3c53bf27522", 79412000),    # the patched insert + a full rebuild
+    ("replay", None): ("replay.hip", "ad5cde5702f702cb", 117363000),
+    ("insert", None): ("replay.hip", "ad5cde5702f702cb", 797000),
+    ("insert", "rebuild"): ("replay.hip", "ad5cde5702f702cb", 79412000),    # the patched insert + a full rebuild
 }
 
 

@@ -856,7 +856,8 @@ __global__ __launch_bounds__(1024) void k_update_small(
     }
 }
 
-// Sampling: a draw is served by a group of 16 lanes, four draws per wave.  Each level of the
+// Sampling: a draw is served by a group of 16 lanes; a wave's four groups take two draws each,
+// level by level side by side (eight draws per wave).  Each level of the
 // index is a non-decreasing run of 256 u64 values searched 16-ary in two probes: lane g of the
 // group first reads the last entry of the g-th run of 16 and the group counts (ballot +
 // popcount) how many are <= t, which selects a run; then the lanes read that run's 16 entries
@@ -884,6 +885,38 @@ __device__ __forceinline__ int search256(const unsigned long long* __restrict__ 
     return chunk < 16 ? 16 * chunk + within : 256;
 }
 
+// D searches of the same kind side by side: the first probes of all of them go out together, then
+// the second probes.  run/coarse/limit of search d: base + first[d], coarse_base + crs[d], nblk - first[d].
+template <int D>
+__device__ __forceinline__ void search256_many(const unsigned long long* __restrict__ base,
+                                               const unsigned long long* __restrict__ coarse_base,
+                                               const int (&first)[D], const int (&crs)[D], int nblk,
+                                               const unsigned long long (&t)[D], int group, int gl,
+                                               int (&rank)[D], unsigned long long (&before)[D]) {
+    unsigned long long va[D], vb[D];
+    int chunk[D];
+    const int ia = 16 * gl + 15;
+#pragma unroll
+    for (int d = 0; d < D; ++d) va[d] = ia < nblk - first[d] ? coarse_base[crs[d] + gl] : ~0ull;
+#pragma unroll
+    for (int d = 0; d < D; ++d) chunk[d] = group_count(va[d] <= t[d], group);          // 0..16
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const int ib = 16 * min(chunk[d], 15) + gl;
+        vb[d] = (chunk[d] < 16 && ib < nblk - first[d]) ? base[first[d] + ib] : ~0ull;
+    }
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const int within = group_count(vb[d] <= t[d], group);                            // 0..15 when chunk < 16
+        const unsigned long long prev_b = __shfl(vb[d], 16 * group + max(within - 1, 0), kWave);
+        const unsigned long long prev_a = __shfl(va[d], 16 * group + max(chunk[d] - 1, 0), kWave);
+        before[d] = within > 0 ? prev_b : (chunk[d] > 0 ? prev_a : 0ull);
+        rank[d] = chunk[d] < 16 ? 16 * chunk[d] + within : 256;
+    }
+}
+
+constexpr int kDrawsPerGroup = 2;   // draws a group of 16 lanes works on at a time
+
 __global__ __launch_bounds__(256) void k_sample(
     const float* __restrict__ weights, long long M, const WsHeader* __restrict__ hdr,
     const unsigned long long* __restrict__ block_cum, int nblk,
@@ -900,58 +933,93 @@ __global__ __launch_bounds__(256) void k_sample(
         if ((threadIdx.x & 15) == 15) super_coarse[threadIdx.x >> 4] = sc;
     }
     __syncthreads();                                 // before any wave may leave
+    constexpr int D = kDrawsPerGroup;
     const int lane = threadIdx.x & 63, group = lane >> 4, gl = lane & 15;
     const int wave_id = (int)(((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (wave_id * 4 >= K) return;                    // whole waves leave together
-    const int k = wave_id * 4 + group;
-    const bool live = k < K;                         // dead groups run along on draw K-1 and store nothing
-    const int kk = live ? k : K - 1;
+    if ((long long)wave_id * (4 * D) >= K) return;   // whole waves leave together
+    // A draw is a chain of five dependent reads; a group walks D chains side by side, level by
+    // level, so that the reads of one level are in flight together.
+    int k[D]; bool live[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        k[d] = (wave_id * 4 + group) * D + d;
+        live[d] = k[d] < K;                          // dead draws run along on draw K-1 and store nothing
+    }
     const unsigned long long total = hdr->total;
     if (total == 0ull) {
-        if (live && gl == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (live[d] && gl == 0) { idx_out[k[d]] = -1; if (prob_out) prob_out[k[d]] = 0.f; }
         return;
     }
-    double u = uniforms[kk];
-    if (!(u >= 0.0)) { u = 0.0; if (live && gl == 0) atomicOr(flags, 0x10u); }
-    // one rounding for the conversion, one for the product, then truncation
-    const double prod = __dmul_rn(u, __ull2double_rn(total));
-    unsigned long long t = (prod >= 18446744073709551616.0) ? total - 1 : (unsigned long long)prod;
-    if (t > total - 1) t = total - 1;
-
+    unsigned long long rem[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        double u = uniforms[live[d] ? k[d] : K - 1];
+        if (!(u >= 0.0)) { u = 0.0; if (live[d] && gl == 0) atomicOr(flags, 0x10u); }
+        // one rounding for the conversion, one for the product, then truncation
+        const double prod = __dmul_rn(u, __ull2double_rn(total));
+        unsigned long long t = (prod >= 18446744073709551616.0) ? total - 1 : (unsigned long long)prod;
+        if (t > total - 1) t = total - 1;
+        rem[d] = t;
+    }
     // level 1: first super-block whose inclusive prefix exceeds t (the padding equals Total > t)
-    unsigned long long before;
-    const int sblk = search256(super_lds, super_coarse, kSuperBlocks, t, group, gl, before);
-    bool stale = sblk >= kSuperBlocks;               // cannot happen with a current index
-    unsigned long long rem = t - (stale ? 0ull : before);
+    bool stale[D]; int first[D], crs[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        unsigned long long before;
+        const int sblk = search256(super_lds, super_coarse, kSuperBlocks, rem[d], group, gl, before);
+        stale[d] = sblk >= kSuperBlocks;             // cannot happen with a current index
+        rem[d] -= stale[d] ? 0ull : before;
+        first[d] = (stale[d] ? 0 : sblk) * kSuperBlocks;
+        crs[d] = (stale[d] ? 0 : sblk) * 16;
+    }
     // level 2: first block of that super-block whose inclusive prefix exceeds the remainder
-    const int first = (stale ? 0 : sblk) * kSuperBlocks;
-    const int within = search256(block_cum + first, coarse_cum + (stale ? 0 : sblk) * 16, nblk - first, rem, group, gl,
-                                 before);
-    stale = stale || within >= kSuperBlocks || first + within >= nblk;
-    const int blk = stale ? 0 : first + within;
-    rem -= stale ? 0ull : before;
-
+    int blk[D];
+    {
+        int within[D]; unsigned long long before[D];
+        search256_many<D>(block_cum, coarse_cum, first, crs, nblk, rem, group, gl, within, before);
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            stale[d] = stale[d] || within[d] >= kSuperBlocks || first[d] + within[d] >= nblk;
+            blk[d] = stale[d] ? 0 : first[d] + within[d];
+            rem[d] -= stale[d] ? 0ull : before[d];
+        }
+    }
     // level 3: the block's 16 sub-block sums, one per lane; the sub-block whose running total
     // first passes the remainder is the one hit
-    const unsigned long long sub = sub_sum[(long long)blk * kSubsPerBlock + gl];
-    const unsigned long long sub_incl = row_scan_u64(sub);       // the 16 lanes of a draw are one DPP row
-    const int owner_sub = group_count(sub_incl <= rem, group);   // lanes whose running total has not passed rem yet
-    // a stale index (weights changed without a rebuild) can run past the end: report -1
-    stale = stale || owner_sub >= kSubsPerBlock;
-    const int hit = stale ? 0 : owner_sub;
-    rem -= stale ? 0ull : __shfl(sub_incl - sub, 16 * group + hit, kWave);
-
+    unsigned long long sub[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) sub[d] = sub_sum[(long long)blk[d] * kSubsPerBlock + gl];
+    int hit[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const unsigned long long sub_incl = row_scan_u64(sub[d]);       // the 16 lanes of a draw are one DPP row
+        const int owner_sub = group_count(sub_incl <= rem[d], group);   // lanes whose running total has not passed rem yet
+        // a stale index (weights changed without a rebuild) can run past the end: report -1
+        stale[d] = stale[d] || owner_sub >= kSubsPerBlock;
+        hit[d] = stale[d] ? 0 : owner_sub;
+        rem[d] -= stale[d] ? 0ull : __shfl(sub_incl - sub[d], 16 * group + hit[d], kWave);
+    }
     // level 4: the sub-block's 16 weights, one per lane
     const int e = exponent_of(hdr->wmax_bits);
-    const long long slot = (long long)blk * kReplayBlock + hit * kSubBlock + gl;
-    const unsigned long long q = quantise(slot < M ? weights[slot] : 0.f, e);
-    const unsigned long long q_incl = row_scan_u64(q);
-    const int owner = group_count(q_incl <= rem, group);
-    if (stale || owner >= kSubBlock) {
-        if (live && gl == 0) { idx_out[k] = -1; if (prob_out) prob_out[k] = 0.f; }
-    } else if (live && gl == owner) {
-        idx_out[k] = slot;
-        if (prob_out) prob_out[k] = (float)((double)q / (double)total);
+    long long slot[D]; float wv[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        slot[d] = (long long)blk[d] * kReplayBlock + hit[d] * kSubBlock + gl;
+        wv[d] = slot[d] < M ? weights[slot[d]] : 0.f;
+    }
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const unsigned long long q = quantise(wv[d], e);
+        const unsigned long long q_incl = row_scan_u64(q);
+        const int owner = group_count(q_incl <= rem[d], group);
+        if (stale[d] || owner >= kSubBlock) {
+            if (live[d] && gl == 0) { idx_out[k[d]] = -1; if (prob_out) prob_out[k[d]] = 0.f; }
+        } else if (live[d] && gl == owner) {
+            idx_out[k[d]] = slot[d];
+            if (prob_out) prob_out[k[d]] = (float)((double)q / (double)total);
+        }
     }
 }
 
@@ -1031,7 +1099,7 @@ hipError_t insert_launch(float* weights, long long M, long long cursor, const fl
 hipError_t sample_launch(const float* weights, long long M, const ReplayWs& w, const double* uniforms, int K,
                          long long* idx_out, float* prob_out, hipStream_t st) {
     const int nblk = (int)((M + kReplayBlock - 1) / kReplayBlock);
-    const long long waves = ((long long)K + 3) / 4;      // four draws per wave
+    const long long waves = ((long long)K + 4 * kDrawsPerGroup - 1) / (4 * kDrawsPerGroup);   // four groups per wave
     const unsigned g = (unsigned)((waves * kWave + 255) / 256);
     hipLaunchKernelGGL(k_sample, dim3(g), dim3(256), 0, st, weights, M, w.hdr, w.block_cum, nblk, w.super_cum,
                        w.sub_sum, w.coarse_cum, uniforms, K, idx_out, prob_out, &w.hdr->flags);
