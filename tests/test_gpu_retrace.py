@@ -455,3 +455,75 @@ def test_scan_results_are_the_same_bits_on_every_run():
     c = fused(lp, lm, si, ent, off, cfg.gamma, cfg.lam, cfg.w)
     for k in a:
         assert torch.equal(a[k].view(torch.int32), c[k].view(torch.int32)), k
+
+
+def test_largest_step_count():
+    # N = 2^31 - 8193, the most steps a call accepts: every 32-bit step index of the scan is
+    # exercised up to its limit.  Constant inputs give closed forms per step: the Monte-Carlo
+    # return of a trajectory of ones is 2 (1 - 2^-m) with m steps left at gamma = 1/2, and the
+    # priority of a step with |delta| = rho = 1 and no entropy is w1/s + w2 + eps.
+    N = (1 << 31) - 8193
+    B = (1 << 20) - 3
+    lens = np.full(B, N // B, np.int64)
+    lens[: N - int(lens.sum())] += 1
+    assert int(lens.sum()) == N
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    off = torch.as_tensor(off_np, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(7)
+    pos = torch.cat([torch.randint(0, N, (1 << 20,), generator=g, device=DEV),
+                     torch.arange(0, 4096, device=DEV), torch.arange(N - 4096, N, device=DEV),
+                     off[:: B // 512].long(), (off[1:: B // 512] - 1).long()])
+    pos_np = npf(pos)
+    traj = np.searchsorted(off_np.astype(np.int64), pos_np, side="right") - 1
+    left = off_np.astype(np.int64)[traj + 1] - pos_np                       # steps left, this one included
+
+    print(f"case mc_returns at N={N}", flush=True)
+    ones = torch.ones(N, device=DEV)
+    ret = torch.full((N,), float("nan"), device=DEV)
+    lab = torch.full((N,), float("nan"), device=DEV)
+    b.mc_returns(ones, off, 0.5, ret=ret, label=lab)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(ret).any()) and not bool(torch.isnan(lab).any()), "a step was not written"
+    want = 2.0 * (1.0 - 0.5 ** np.minimum(left, 200).astype(np.float64))
+    assert_close(npf(ret[pos]), want, 1.0, "mc return at the largest N")
+    assert bool((lab[pos] == 1).all())
+    del ret, lab
+
+    print(f"case compute_priorities at N={N}", flush=True)
+    zeros = torch.zeros(N, device=DEV)
+    sp = torch.full((N,), float("nan"), device=DEV)
+    tp = torch.full((B,), float("nan"), device=DEV)
+    b.compute_priorities(ones, ones, zeros, off, (1.0, 0.5, 0.1), td_scale=2.0, ent_scale=8.0, eps=1e-3, step_prio=sp,
+                         traj_prio=tp)
+    torch.cuda.synchronize()
+    c = 1.0 / 2.0 + 0.5 + 1e-3
+    assert not bool(torch.isnan(sp).any()) and not bool(torch.isnan(tp).any()), "a priority was not written"
+    assert_close(npf(sp[pos]), np.full(pos_np.shape, c), 1.0, "step priority at the largest N")
+    assert_close(npf(tp), np.full(B, c), 1.0, "trajectory priority at the largest N")
+
+    print(f"case retrace_priorities at N={N}", flush=True)
+    # pi = mu (ratio 1), reward 1, values 0, gamma 1/2, lambda 1: delta = 1 and the correction is the
+    # Monte-Carlo sum again; the priority 1/2 * |1| / 2... = w1 * 1/s + w2 * 1 + eps as above
+    del sp, tp
+    out = {k: torch.full((N,), float("nan"), device=DEV) for k in ("target", "td", "rho", "step_prio")}
+    tp = torch.full((B,), float("nan"), device=DEV)
+    b.retrace_priorities(zeros, zeros, ones, zeros, zeros, off, 0.5, 1.0, (1.0, 0.5, 0.1), td_scale=2.0, ent_scale=8.0,
+                         eps=1e-3, traj_prio=tp, **out)
+    torch.cuda.synchronize()
+    for k, v in out.items():
+        assert not bool(torch.isnan(v).any()), f"{k}: a step was not written"
+    assert_close(npf(out["target"][pos]), want, 1.0, "target at the largest N")
+    assert bool((out["td"][pos] == 1).all()) and bool((out["rho"][pos] == 1).all())
+    assert_close(npf(out["step_prio"][pos]), np.full(pos_np.shape, c), 1.0, "one-pass step priority at the largest N")
+    assert_close(npf(tp), np.full(B, c), 1.0, "one-pass trajectory priority at the largest N")
+
+
+def test_largest_trajectory_count(oracle):
+    # B = 2^25 - 1, the most trajectories a call accepts (lengths 0, 1 or 2): trajectory numbers fill
+    # the marks' 25 bits, and every chunk is touched by about 250 trajectories
+    B = (1 << 25) - 1
+    rng = np.random.default_rng(25)
+    lens = rng.integers(0, 3, B)
+    print(f"case {B} trajectories, {int(lens.sum())} steps", flush=True)
+    off_np = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    one_pass_against_oracle(oracle, off_np, 2525, 0.9, 0.95, "largest B")
