@@ -32,11 +32,11 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # the file's sha256) and for its workload; anything else reports null.
 TRAFFIC = {
     # the logit sweep (k_score_rows_split) on configs 0, 1, 2
-    ("scoring", 0): ("score_logits.hip", "8d90504f0b1d88a8", 164830208),
-    ("scoring", 1): ("score_logits.hip", "8d90504f0b1d88a8", 5287656550),
-    ("scoring", 2): ("score_logits.hip", "8d90504f0b1d88a8", 39844482458),
+    ("scoring", 0): ("score_logits.hip", "ec8dc28141d1f500", 164830618),
+    ("scoring", 1): ("score_logits.hip", "ec8dc28141d1f500", 5287704064),
+    ("scoring", 2): ("score_logits.hip", "ec8dc28141d1f500", 39843860582),
     # k_actor_grad on config 1
-    ("actor_grad", 1): ("actor_grad.hip", "53dcf17a0ee283d4", 10559417139),
+    ("actor_grad", 1): ("actor_grad.hip", "afc03ce463a348c2", 10559418982),
     # k_flat_scan on config 3 at batch scales 1, 16, 64: (scale, one pass?)
     ("retrace", (1, True)): ("retrace.hip", "c321b09416a5e31a", 26570957),
     ("retrace", (16, True)): ("retrace.hip", "c321b09416a5e31a", 439354368),

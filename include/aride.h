@@ -51,7 +51,7 @@ extern "C" {
 #define ARIDE_ST_BAD_UNIFORM 0x10u /* a uniform < 0 or NaN was read as 0 */
 
 #define ARIDE_MAX_REPLAY (1 << 24) /* largest M: keeps the integer CDF below 2^63 */
-#define ARIDE_MAX_ROWS 8589934528LL       /* largest R of the logit sweeps: 2^33 - 64 (four rows to a workgroup, 2^31 - 16 workgroups) */
+#define ARIDE_MAX_ROWS 8589934528LL       /* largest R of the logit sweeps: 2^33 - 64 (more rows than one launch covers go out as several) */
 #define ARIDE_MAX_STEPS 2147475455LL      /* largest N of the scan calls: 2^31 - 1 - 8192 (a chunk of steps past N still indexes as int32) */
 #define ARIDE_MAX_TRAJECTORIES 33554431LL /* largest B of the scan calls: 2^25 - 1 */
 
@@ -260,7 +260,7 @@ int aride_update_priorities(float* weights, int64_t M, const int64_t* idx, const
  *
  *  weights fp32 [M] in/out (16-byte aligned); cursor in [0, M); prio fp32 [K];
  *  slots_out int64 [K] nullable; cursor_out host pointer, nullable: receives (cursor + K) mod M.
- * Errors: E_NULL, E_SHAPE, E_ALIGN, E_RANGE (cursor outside [0,M), alpha < 0, K > 2^38), E_WORKSPACE.
+ * Errors: E_NULL, E_SHAPE, E_ALIGN, E_RANGE (cursor outside [0,M), alpha < 0, K > 2^31 - 256), E_WORKSPACE.
  */
 int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* prio, int64_t K,
                         float alpha, int64_t* slots_out, void* ws, size_t ws_bytes,

@@ -60,7 +60,7 @@ __device__ __forceinline__ uint16_t pack_bf16_one(float v) {
 // 16 out) for fp32 output, so that every store instruction of a wave writes 1 KB without gaps.
 template <bool OUT_F32, int WPR>
 __global__ __launch_bounds__(WPR == 1 ? 256 : 64 * WPR) void k_actor_grad(
-    const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
+    const uint16_t* __restrict__ logits, long long row0, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, int A, const float* __restrict__ tok_logp,
     const float* __restrict__ tok_ent, const float* __restrict__ rho, const float* __restrict__ target,
     const float* __restrict__ baseline, float beta, float scale, void* __restrict__ grad_out) {
@@ -69,8 +69,8 @@ __global__ __launch_bounds__(WPR == 1 ? 256 : 64 * WPR) void k_actor_grad(
     constexpr uint32_t kVecBytes = 2 * kVec;
     typedef uint32_t vec_t __attribute__((ext_vector_type(kWords)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long row = WPR == 1 ? (((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6)
-                                   : xcd_contiguous_block();   // the grid is R rounded up to a multiple of 8
+    const long long row = row0 + (WPR == 1 ? (((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6)
+                                           : xcd_contiguous_block());   // the grid: this launch's rows, rounded up to a multiple of 8
     if (row >= R) return;   // whole waves (WPR = 1) or the whole workgroup leave; there is no barrier below
     const int tok = tokens[row];
     const bool live = tok >= 0 && tok < V;
@@ -193,16 +193,20 @@ hipError_t actor_launch(const uint16_t* logits, long long R, int V, long long st
                         const float* baseline, const float* penalty, float beta, float lambda_pen,
                         float scale, int grad_f32, void* grad, float* loss, hipStream_t st) {
     if (grad && R > 0) {
-        // rows of 16 KB and more: a workgroup of 8 waves per row, of 24 KB and more: of 16 waves
-        // (one workgroup per row must fit the grid)
-        const int wpr = (R > 0x7ffffff0ll || V < kSplit8MinV) ? 1 : V < kSplit16MinV ? 8 : 16;
-        const dim3 grid(wpr > 1 ? round_up_8((unsigned)R) : (unsigned)((R + 3) / 4));
-        auto go = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, grid, dim3(wpr > 1 ? 64 * wpr : 256), 0, st, logits, R, V, stride, tokens, A,
-                               tok_logp, tok_ent, rho, target, baseline, beta, scale, grad);
-        };
-        if (grad_f32) { if (wpr == 16) go(k_actor_grad<true, 16>); else if (wpr == 8) go(k_actor_grad<true, 8>); else go(k_actor_grad<true, 1>); }
-        else          { if (wpr == 16) go(k_actor_grad<false, 16>); else if (wpr == 8) go(k_actor_grad<false, 8>); else go(k_actor_grad<false, 1>); }
+        // rows of 16 KB and more: a workgroup of 8 waves per row, of 24 KB and more: of 16 waves.
+        // A launch covers at most kMaxLaunchThreads work-items; more rows go out slice by slice.
+        const int wpr = V < kSplit8MinV ? 1 : V < kSplit16MinV ? 8 : 16;
+        const long long slice = kMaxLaunchThreads / (64 * wpr);
+        for (long long row0 = 0; row0 < R; row0 += slice) {
+            const long long rows = R - row0 < slice ? R - row0 : slice;
+            const dim3 grid(wpr > 1 ? round_up_8((unsigned)rows) : (unsigned)((rows + 3) / 4));
+            auto go = [&](auto kernel) {
+                hipLaunchKernelGGL(kernel, grid, dim3(wpr > 1 ? 64 * wpr : 256), 0, st, logits, row0, R, V, stride, tokens,
+                                   A, tok_logp, tok_ent, rho, target, baseline, beta, scale, grad);
+            };
+            if (grad_f32) { if (wpr == 16) go(k_actor_grad<true, 16>); else if (wpr == 8) go(k_actor_grad<true, 8>); else go(k_actor_grad<true, 1>); }
+            else          { if (wpr == 16) go(k_actor_grad<false, 16>); else if (wpr == 8) go(k_actor_grad<false, 8>); else go(k_actor_grad<false, 1>); }
+        }
     }
     if (loss)
         hipLaunchKernelGGL(k_actor_loss, dim3(1), dim3(1024), 0, st, step_logp, step_ent, rho, target, baseline,

@@ -225,7 +225,7 @@ int aride_replay_insert(float* weights, int64_t M, int64_t cursor, const float* 
     if (K < 0) return ARIDE_E_SHAPE;
     int rc = check_replay(weights, M, ws, ws_bytes);
     if (rc != ARIDE_OK) return rc;
-    if (cursor < 0 || cursor >= M || !(alpha >= 0.f) || K > ((int64_t)1 << 38)) return ARIDE_E_RANGE;   // k_insert's grid
+    if (cursor < 0 || cursor >= M || !(alpha >= 0.f) || K > kMaxLaunchThreads - 256) return ARIDE_E_RANGE;   // k_insert: a thread per entry, one launch
     if (K > 0 && !prio) return ARIDE_E_NULL;
     if (slots_out && misaligned(slots_out, 8)) return ARIDE_E_ALIGN;
     hipError_t err = insert_launch(weights, M, cursor, prio, K, alpha, (long long*)slots_out, replay_ws(ws, M),

@@ -109,6 +109,10 @@ __device__ __forceinline__ long long xcd_contiguous_block() {
 }
 inline unsigned round_up_8(unsigned blocks) { return (blocks + 7u) / 8u * 8u; }
 
+// A dispatch counts its work-items per dimension in 32 bits (more wrap around without an error):
+// a launch is given at most 2^31 of them, and work beyond that goes out as several launches.
+constexpr long long kMaxLaunchThreads = 1ll << 31;
+
 // Cross-lane moves inside a row of 16 lanes as DPP operands of ordinary vector instructions (no
 // trip through the LDS crossbar, which is what __shfl costs).  CTRL: 0x120 | n rotates the row
 // by n lanes, 0x110 | n shifts it right by n (lanes without a source read 0), 0x00..0xFF permute

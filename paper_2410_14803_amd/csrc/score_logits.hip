@@ -133,13 +133,13 @@ __device__ __forceinline__ void to_common(float negk, float s, float t, float kc
 
 template <int UNROLL>
 __global__ __launch_bounds__(64 * kScoreWaves) void k_score_rows(
-    const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
+    const uint16_t* __restrict__ logits, long long row0, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
     const int lane = threadIdx.x & 63;
     // the grid is a multiple of 8 and XCD x takes the x-th eighth of the rows: each XCD, with its own
     // L2 and its own paths to memory, streams one contiguous region instead of every eighth 256 KB
-    const long long row = xcd_contiguous_block() * kScoreWaves + (threadIdx.x >> 6);
+    const long long row = row0 + xcd_contiguous_block() * kScoreWaves + (threadIdx.x >> 6);   // this launch: rows row0 ..
     if (row >= R) return;   // whole waves leave together; the kernel has no workgroup barrier
 
     const int tok = tokens[row];
@@ -208,12 +208,12 @@ __global__ __launch_bounds__(64 * kScoreWaves) void k_score_rows(
 // waves per SIMD).
 template <int UNROLL, int WPR>
 __global__ __launch_bounds__(64 * WPR) void k_score_rows_split(
-    const uint16_t* __restrict__ logits, long long R, int V, long long row_stride,
+    const uint16_t* __restrict__ logits, long long row0, long long R, int V, long long row_stride,
     const int* __restrict__ tokens, float* __restrict__ tok_logp, float* __restrict__ tok_ent,
     uint32_t* __restrict__ status) {
     __shared__ float part[WPR][3];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long row = xcd_contiguous_block();   // the grid is R rounded up to a multiple of 8
+    const long long row = row0 + xcd_contiguous_block();   // the grid is this launch's rows rounded up to a multiple of 8
     if (row >= R) return;                           // the whole workgroup leaves
 
     const int tok = tokens[row];
@@ -335,22 +335,26 @@ hipError_t score_logits_launch(const uint16_t* logits, long long R, int V, long 
                                hipEvent_t sweep_start, hipEvent_t sweep_stop) {
     constexpr int U = kScoreUnroll;
     const int nvec = V >> 3;                                  // 16-byte vectors per row
-    const bool fits_grid = R <= 0x7ffffff0ll;                 // one workgroup per row
-    const dim3 rows8(round_up_8((unsigned)(fits_grid ? R : 0)));
-    if (fits_grid && nvec >= kSplit16MinVec)
-        launch_sweep(k_score_rows_split<U, 16>, rows8, dim3(1024), st, sweep_start, sweep_stop, logits, R, V, stride,
-                     tokens, tok_logp, tok_ent, status);
-    else if (fits_grid && nvec >= kSplit8MinVec)
-        launch_sweep(k_score_rows_split<U, 8>, rows8, dim3(512), st, sweep_start, sweep_stop, logits, R, V, stride,
-                     tokens, tok_logp, tok_ent, status);
-    else if (fits_grid && nvec >= kSplit4MinVec)
-        launch_sweep(k_score_rows_split<U, 4>, rows8, dim3(256), st, sweep_start, sweep_stop, logits, R, V, stride,
-                     tokens, tok_logp, tok_ent, status);
-    else {
-        long long blocks = (R + kScoreWaves - 1) / kScoreWaves;       // R <= 2^33 - 64 (checked by the caller)
-        blocks = (blocks + 7) / 8 * 8;                       // the kernel's row mapping wants a multiple of 8
-        launch_sweep(k_score_rows<U>, dim3((unsigned)blocks), dim3(64 * kScoreWaves), st, sweep_start,
-                     sweep_stop, logits, R, V, stride, tokens, tok_logp, tok_ent, status);
+    const int wpr = nvec >= kSplit16MinVec ? 16 : nvec >= kSplit8MinVec ? 8 : nvec >= kSplit4MinVec ? 4 : 1;
+    // rows one launch may cover (64 work-items per row and wave); more rows go out slice by slice,
+    // the events, when given, on the first and the last slice
+    const long long slice = kMaxLaunchThreads / (64 * wpr);
+    for (long long row0 = 0; row0 < R; row0 += slice) {
+        const long long rows = R - row0 < slice ? R - row0 : slice;
+        hipEvent_t ev0 = row0 == 0 ? sweep_start : nullptr, ev1 = row0 + rows >= R ? sweep_stop : nullptr;
+        const dim3 rows8(round_up_8((unsigned)rows));
+        if (wpr == 16)
+            launch_sweep(k_score_rows_split<U, 16>, rows8, dim3(1024), st, ev0, ev1, logits, row0, R, V, stride, tokens,
+                         tok_logp, tok_ent, status);
+        else if (wpr == 8)
+            launch_sweep(k_score_rows_split<U, 8>, rows8, dim3(512), st, ev0, ev1, logits, row0, R, V, stride, tokens,
+                         tok_logp, tok_ent, status);
+        else if (wpr == 4)
+            launch_sweep(k_score_rows_split<U, 4>, rows8, dim3(256), st, ev0, ev1, logits, row0, R, V, stride, tokens,
+                         tok_logp, tok_ent, status);
+        else
+            launch_sweep(k_score_rows<U>, dim3(round_up_8((unsigned)((rows + kScoreWaves - 1) / kScoreWaves))),
+                         dim3(64 * kScoreWaves), st, ev0, ev1, logits, row0, R, V, stride, tokens, tok_logp, tok_ent, status);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!step_logp && !step_ent)) return err;

@@ -149,6 +149,7 @@ def test_replay_rejects_bad_arguments(L):
     assert ins(w, 1000, 0, a, -1, 0.6, None, ws, need, None, None) == b.E_SHAPE
     assert ins(w, 1000, 1000, a, 4, 0.6, None, ws, need, None, None) == b.E_RANGE     # cursor outside the buffer
     assert ins(w, 1000, -1, a, 4, 0.6, None, ws, need, None, None) == b.E_RANGE
+    assert ins(w, 1000, 0, a, (1 << 31) - 255, 0.6, None, ws, need, None, None) == b.E_RANGE   # more entries than one launch's threads
     assert ins(w, 1000, 0, None, 4, 0.6, None, ws, need, None, None) == b.E_NULL
     assert ins(w, 1000, 0, a, 4, 0.6, None, ws, need - 1, None, None) == b.E_WORKSPACE
     assert ins(w, 1000, 0, a, 4, 0.6, P(16388), ws, need, None, None) == b.E_ALIGN

@@ -201,3 +201,24 @@ def test_config1_full_size_every_row(oracle):
     worst = max(r[1] for r in results)
     print(f"worst ratio to the bound {worst:.3f}", flush=True)
     assert bad == 0, f"{bad} gradient elements beyond one bf16 ulp plus the inherited bound; worst ratio {worst:.3f}"
+
+
+def test_more_rows_than_one_launch_covers():
+    # two-logit rows take one wave each and a launch covers 2^25 of them: 2^25 + 4 rows take two.
+    # Uniform rows, rho * A = 1, scale 1: the gradient is -1/2 at the token and +1/2 beside it.
+    R, V, A = (1 << 25) + 4, 2, 4
+    N = R // A
+    print(f"case actor R={R} V={V}", flush=True)
+    logits = torch.zeros((R, V), dtype=torch.bfloat16, device=DEV)
+    tokens = torch.zeros(R, dtype=torch.int32, device=DEV)
+    tokens[-1] = 1
+    fp = first_pass(logits, tokens, A)
+    one, zero = torch.ones(N, device=DEV), torch.zeros(N, device=DEV)
+    g32 = torch.full((R, V), float("nan"), device=DEV)
+    b.actor_loss_grad(logits, tokens, A, fp["tok_logp"], fp["tok_ent"], fp["step_logp"], fp["step_ent"], one, one, zero,
+                      0.01, 1.0, grad=g32)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(g32).any()), "a row was not written"
+    body = g32[:-1]
+    assert float((body[:, 0] + 0.5).abs().max()) < 1e-6 and float((body[:, 1] - 0.5).abs().max()) < 1e-6
+    assert abs(float(g32[-1, 1]) + 0.5) < 1e-6 and abs(float(g32[-1, 0]) - 0.5) < 1e-6

@@ -464,6 +464,9 @@ def test_largest_step_count():
     # priority of a step with |delta| = rho = 1 and no entropy is w1/s + w2 + eps.
     N = (1 << 31) - 8193
     B = (1 << 20) - 3
+    torch.cuda.empty_cache()
+    if torch.cuda.mem_get_info()[0] < (80 << 30):
+        pytest.skip("needs 60 GB of free device memory")
     lens = np.full(B, N // B, np.int64)
     lens[: N - int(lens.sum())] += 1
     assert int(lens.sum()) == N

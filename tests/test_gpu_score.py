@@ -246,3 +246,54 @@ def test_row_lengths_where_the_number_of_waves_per_row_changes(oracle, V):
     want = oracle.score_logits(bits_of(logits), npf(tokens), A, V=V, nthreads=8)
     compare(got, want, V, A, f"V={V}")
     assert flags == 0
+
+
+def test_more_rows_than_32_bits_count():
+    # R = 2^31 + 4096 rows of two logits: row numbers and row offsets beyond 32 bits.  Equal logits
+    # make every row uniform: log p = -ln 2, H = ln 2.
+    R, V = (1 << 31) + 4096, 2
+    torch.cuda.empty_cache()
+    if torch.cuda.mem_get_info()[0] < (60 << 30):
+        pytest.skip("needs 40 GB of free device memory")
+    print(f"case R={R} V={V}", flush=True)
+    logits = torch.zeros((R, V), dtype=torch.bfloat16, device=DEV)
+    logits[-1, 1] = 3.0                                # the last row is not uniform: it must be reached, and only it
+    tokens = torch.zeros(R, dtype=torch.int32, device=DEV)
+    ws = b.Workspace(0)
+    lp = torch.full((R,), float("nan"), device=DEV)
+    en = torch.full((R,), float("nan"), device=DEV)
+    b.score_logits(logits, tokens, 128, ws, tok_logp=lp, tok_ent=en)      # 2^24 + 32 steps of 128 tokens
+    torch.cuda.synchronize()
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0
+    ln2 = float(np.log(2.0))
+    body_lp, body_en = lp[:-1], en[:-1]
+    assert float(body_lp.min()) == float(body_lp.max()) and abs(float(body_lp[0]) + ln2) < 1e-6
+    assert float(body_en.min()) == float(body_en.max()) and abs(float(body_en[0]) - ln2) < 1e-6
+    z = np.log(1.0 + np.exp(3.0))
+    p1 = np.exp(3.0 - z)
+    assert abs(float(lp[-1]) - (0.0 - z)) < 1e-5
+    assert abs(float(en[-1]) - (-(1 - p1) * np.log(1 - p1) - p1 * np.log(p1))) < 1e-5
+
+
+def test_more_rows_than_one_launch_covers_with_several_waves_per_row():
+    # 8192-logit rows are shared by 4 waves: a launch covers 2^23 of them; 2^23 + 24 rows take two.
+    # Uniform rows: log p = -ln V, H = ln V; the last row carries one larger logit.
+    R, V = (1 << 23) + 24, 8192
+    torch.cuda.empty_cache()
+    if torch.cuda.mem_get_info()[0] < (180 << 30):
+        pytest.skip("needs 140 GB of free device memory")
+    print(f"case R={R} V={V}", flush=True)
+    logits = torch.zeros((R, V), dtype=torch.bfloat16, device=DEV)
+    logits[-1, 5] = 4.0
+    tokens = torch.zeros(R, dtype=torch.int32, device=DEV)
+    ws = b.Workspace(0)
+    lp = torch.full((R,), float("nan"), device=DEV)
+    en = torch.full((R,), float("nan"), device=DEV)
+    b.score_logits(logits, tokens, 8, ws, tok_logp=lp, tok_ent=en)
+    torch.cuda.synchronize()
+    lnv = float(np.log(V))
+    assert float(lp[:-1].min()) == float(lp[:-1].max()) and abs(float(lp[0]) + lnv) < 1e-5
+    assert float(en[:-1].min()) == float(en[:-1].max()) and abs(float(en[0]) - lnv) < 1e-5
+    z = np.log(V - 1 + np.exp(4.0))
+    assert abs(float(lp[-1]) + z) < 1e-5
