@@ -91,7 +91,7 @@ static void mix_launch(const f32x4* const* ins, f32x4* const* outs, size_t nvec,
 // (nin, nout) in {(6,4), (5,3), (3,1), (6,0), (0,4)}; pattern: bit 0 = non-temporal loads,
 // bit 1 = a contiguous span per wave instead of a workgroup per 4 KB.
 extern "C" int aride_probe_mix(const void* in, void* out, int nin, int nout, size_t n, int pattern, void* stream) {
-    if (!in || !out || (n & 3) || pattern < 0 || pattern > 3 || n > ((size_t)1 << 36)) return -1;
+    if (!in || !out || (n & 3) || pattern < 0 || pattern > 3 || n > ((size_t)1 << 33)) return -1;   // a work-item per 16 bytes, at most 2^31 a launch
     const size_t nvec = n / 4;
     if (nvec == 0) return 0;
     auto ins = (const f32x4* const*)in;
