@@ -174,7 +174,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void k_score_rows(
             float x[1] = {bits_to_float(((uint32_t)p[lane]) << 16)};
             lane_accumulate<1>(a, x);
         }
-        if (tail0 + lane < V) {   // fewer than 8 elements remain
+        if (lane < V - tail0) {   // fewer than 8 elements remain (not tail0 + lane < V: that sum can pass 2^31)
             float x[1] = {bits_to_float(((uint32_t)p[tail0 + lane]) << 16)};
             lane_accumulate<1>(a, x);
         }
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(64 * WPR) void k_score_rows_split(
                 float x[1] = {bits_to_float(((uint32_t)p[lane]) << 16)};
                 lane_accumulate<1>(a, x);
             }
-            if (tail0 + lane < V) {
+            if (lane < V - tail0) {   // (not tail0 + lane < V: that sum can pass 2^31)
                 float x[1] = {bits_to_float(((uint32_t)p[tail0 + lane]) << 16)};
                 lane_accumulate<1>(a, x);
             }

@@ -222,3 +222,28 @@ def test_more_rows_than_one_launch_covers():
     body = g32[:-1]
     assert float((body[:, 0] + 0.5).abs().max()) < 1e-6 and float((body[:, 1] - 0.5).abs().max()) < 1e-6
     assert abs(float(g32[-1, 1]) + 0.5) < 1e-6 and abs(float(g32[-1, 0]) - 0.5) < 1e-6
+
+
+def test_longest_row():
+    # V = 2^31 - 1 logits in a row, the most a call accepts: element numbers up to the 32-bit limit.
+    # A uniform row with rho * A = 1 and scale 1: every gradient element is 1/V but the token's,
+    # which is 1/V - 1 (the entropy term vanishes: log p + H = 0).
+    V = (1 << 31) - 1
+    stride = 1 << 31
+    torch.cuda.empty_cache()
+    if torch.cuda.mem_get_info()[0] < (24 << 30):
+        pytest.skip("needs 10 GB of free device memory")
+    print(f"case actor V={V}", flush=True)
+    logits = torch.zeros((1, stride), dtype=torch.bfloat16, device=DEV)
+    tokens = torch.tensor([V - 1], dtype=torch.int32, device=DEV)
+    fp = first_pass(logits, tokens, 1, V=V)
+    one, zero = torch.ones(1, device=DEV), torch.zeros(1, device=DEV)
+    g16 = torch.full((1, stride), 7.0, dtype=torch.bfloat16, device=DEV)
+    b.actor_loss_grad(logits, tokens, 1, fp["tok_logp"], fp["tok_ent"], fp["step_logp"], fp["step_ent"], one, one, zero,
+                      0.01, 1.0, grad=g16, V=V)
+    torch.cuda.synchronize()
+    body = g16[0, : V - 1].float()
+    assert float(body.min()) == float(body.max())
+    assert abs(float(body[0]) * V - 1.0) < 2.0 ** -7 + 1e-3          # one bf16 ulp, and the first sweep's log Z
+    assert abs(float(g16[0, V - 1]) + 1.0) < 2.0 ** -7
+    assert float(g16[0, V]) == 7.0                                    # the column past the row is untouched

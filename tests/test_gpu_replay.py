@@ -313,3 +313,37 @@ def test_update_overwrites_slots_that_hold_bad_bits(oracle, M, K, duplicates):
     st, rc = ws.status()
     assert rc == b.OK and not st.flags & b.ST_BAD_WEIGHT     # nothing bad is left in the buffer
     check_sample(oracle, w, synth.uniforms(1000, 61, DEV), ws, "after overwriting bad slots")
+
+
+def test_largest_update_batch_and_largest_draw(oracle):
+    # K = 2^23 - 1 updates (the tags' 23 bits filled) with heavy repetition on the largest buffer,
+    # then K = 2^25 - 1 draws: all indices in range, the first and last 40 000 bit for bit
+    M = 1 << 24
+    K = (1 << 23) - 1
+    print(f"case update K={K} M={M}", flush=True)
+    w = torch.as_tensor(np.random.default_rng(1).random(M, dtype=np.float32) + 0.01, device=DEV)
+    ws = b.Workspace(M)
+    g = torch.Generator(device=DEV); g.manual_seed(11)
+    idx = torch.randint(0, M // 8, (K,), generator=g, device=DEV)       # about four occurrences per slot
+    idx[-1] = 5; idx[0] = 5; idx[K // 2] = M - 1
+    prio = torch.rand(K, generator=g, device=DEV) * 3
+    wo = npf(w).copy()
+    b.update_priorities(w, idx, prio, 0.6, ws)
+    torch.cuda.synchronize()
+    oracle.update_priorities(wo, npf(idx), npf(prio), 0.6)
+    np.testing.assert_allclose(npf(w), wo, rtol=1e-6, atol=0, err_msg="weights after the largest update batch")
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0
+
+    Kd = (1 << 25) - 1
+    print(f"case sample K={Kd}", flush=True)
+    u = synth.uniforms(Kd, 12, DEV)
+    out = torch.full((Kd,), -7, dtype=torch.int64, device=DEV)
+    b.sample_prioritized(w, u, ws, out, None)
+    torch.cuda.synchronize()
+    assert int(out.min()) >= 0 and int(out.max()) < M
+    assert bool((w[out] > 0).all())
+    wh = npf(w)
+    for sl in (slice(0, 40000), slice(Kd - 40000, Kd)):
+        oi, _, _ = oracle.sample_prioritized(wh, npf(u[sl]))
+        np.testing.assert_array_equal(npf(out[sl]), oi, err_msg="indices of the largest draw")

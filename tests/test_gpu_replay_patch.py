@@ -238,3 +238,29 @@ def test_large_buffer_extreme_magnitudes(oracle, top):
     prio = (rng.random(5000) * top * 0.5).astype(np.float32)
     insert(oracle, w, ws, M - 2000, prio, alpha=1.0)
     check(oracle, w, ws, 301, f"top={top} after insert")
+
+
+def test_largest_insert_batch():
+    # K = 2^31 - 256 entries, the most one call accepts, into a buffer of 2^20: what inserting them one
+    # by one would leave are the last M of them; every earlier entry reports slot -1
+    M = 1 << 20
+    K = (1 << 31) - 256
+    torch.cuda.empty_cache()
+    if torch.cuda.mem_get_info()[0] < (40 << 30):
+        pytest.skip("needs 26 GB of free device memory")
+    print(f"case insert K={K} M={M}", flush=True)
+    w = torch.zeros(M, device=DEV)
+    ws = b.Workspace(M)
+    prio = (torch.arange(K, device=DEV, dtype=torch.int32) % 7 + 1).float()      # 1 .. 7, period 7
+    slots = torch.full((K,), -7, dtype=torch.int64, device=DEV)
+    cursor = b.replay_insert(w, 12345, prio, 1.0, ws, slots_out=slots)           # alpha = 1 stores the priorities as they are
+    torch.cuda.synchronize()
+    assert cursor == (12345 + K) % M
+    assert bool((slots[: K - M] == -1).all())
+    k_last = torch.arange(K - M, K, device=DEV, dtype=torch.int64)
+    assert bool((slots[K - M:] == (12345 + k_last) % M).all())
+    want = torch.empty(M, device=DEV)
+    want[(12345 + k_last) % M] = prio[K - M:]
+    assert torch.equal(w, want)
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0

@@ -297,3 +297,33 @@ def test_more_rows_than_one_launch_covers_with_several_waves_per_row():
     assert float(en[:-1].min()) == float(en[:-1].max()) and abs(float(en[0]) - lnv) < 1e-5
     z = np.log(V - 1 + np.exp(4.0))
     assert abs(float(lp[-1]) + z) < 1e-5
+
+
+def test_longest_row():
+    # V = 2^31 - 1 logits in a row, the most a call accepts (two rows): element numbers inside a row
+    # run up to the 32-bit limit.  Uniform rows: log p = -ln V, H = ln V; the second row has one
+    # logit 20 above the rest at the very end, and that is its token.
+    V = (1 << 31) - 1
+    stride = 1 << 31
+    torch.cuda.empty_cache()
+    if torch.cuda.mem_get_info()[0] < (20 << 30):
+        pytest.skip("needs 9 GB of free device memory")
+    print(f"case V={V}", flush=True)
+    logits = torch.zeros((2, stride), dtype=torch.bfloat16, device=DEV)
+    logits[1, V - 1] = 20.0
+    logits[:, V:] = 50.0                                  # beyond the row: must not be read
+    tokens = torch.tensor([7, V - 1], dtype=torch.int32, device=DEV)
+    ws = b.Workspace(0)
+    lp = torch.full((2,), float("nan"), device=DEV)
+    en = torch.full((2,), float("nan"), device=DEV)
+    b.score_logits(logits, tokens, 1, ws, tok_logp=lp, tok_ent=en, V=V)
+    torch.cuda.synchronize()
+    st, rc = ws.status()
+    assert rc == b.OK and st.flags == 0
+    lnv = float(np.log(float(V)))
+    assert abs(float(lp[0]) + lnv) < 1e-4 * lnv and abs(float(en[0]) - lnv) < 1e-4 * lnv
+    z = np.log(float(V - 1) + np.exp(20.0))
+    p1 = np.exp(20.0 - z)
+    h = -(V - 1) * np.exp(-z) * (-z) - p1 * np.log(p1)
+    assert abs(float(lp[1]) - (20.0 - z)) < 1e-4 * abs(20.0 - z) + 1e-6
+    assert abs(float(en[1]) - h) < 1e-4 * h
