@@ -32,9 +32,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # the file's sha256) and for its workload; anything else reports null.
 TRAFFIC = {
     # the logit sweep (k_score_rows_split) on configs 0, 1, 2
-    ("scoring", 0): ("score_logits.hip", "ec8dc28141d1f500", 164830618),
-    ("scoring", 1): ("score_logits.hip", "ec8dc28141d1f500", 5287704064),
-    ("scoring", 2): ("score_logits.hip", "ec8dc28141d1f500", 39843860582),
+    ("scoring", 0): ("score_logits.hip", "44710732453a7cf8", 164830618),
+    ("scoring", 1): ("score_logits.hip", "44710732453a7cf8", 5287676621),
+    ("scoring", 2): ("score_logits.hip", "44710732453a7cf8", 39844374118),
     # k_actor_grad on config 1
     ("actor_grad", 1): ("actor_grad.hip", "afc03ce463a348c2", 10559418982),
     # k_flat_scan on config 3 at batch scales 1, 16, 64: (scale, one pass?)
