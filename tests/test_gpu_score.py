@@ -327,3 +327,24 @@ def test_longest_row():
     h = -(V - 1) * np.exp(-z) * (-z) - p1 * np.log(p1)
     assert abs(float(lp[1]) - (20.0 - z)) < 1e-4 * abs(20.0 - z) + 1e-6
     assert abs(float(en[1]) - h) < 1e-4 * h
+
+
+def test_most_steps_and_longest_step():
+    # R / A = 2^25 - 1 steps of one token (the most the per-step sums accept), and two steps of 2^20
+    # tokens each: per-step values are the sums of the per-token ones
+    for R, A in (((1 << 25) - 1, 1), (1 << 21, 1 << 20)):
+        print(f"case R={R} A={A}", flush=True)
+        V = 2
+        logits = torch.zeros((R, V), dtype=torch.bfloat16, device=DEV)
+        tokens = torch.zeros(R, dtype=torch.int32, device=DEV)
+        ws = b.Workspace(0)
+        N = R // A
+        out = dict(tok_logp=torch.full((R,), float("nan"), device=DEV), tok_ent=torch.full((R,), float("nan"), device=DEV),
+                   step_logp=torch.full((N,), float("nan"), device=DEV), step_ent=torch.full((N,), float("nan"), device=DEV))
+        b.score_logits(logits, tokens, A, ws, **out)
+        torch.cuda.synchronize()
+        ln2 = float(np.log(2.0))
+        for k, sign in (("step_logp", -1.0), ("step_ent", 1.0)):
+            v = out[k]
+            assert float(v.min()) == float(v.max()), k
+            assert abs(float(v[0]) - sign * A * ln2) <= 1e-6 * A * ln2, k
